@@ -1,0 +1,11 @@
+"""MI355X-native hot path of AAAC: activation importance, weighted Lloyd
+iterations learning two 16-entry codebooks, 4-bit encode and dequant, as HIP
+kernels for gfx950 behind a C ABI (include/aaac.h).
+
+The functions re-exported here only marshal arguments into that library; they
+raise if it has not been built.
+"""
+from .binding import (  # noqa: F401
+    AaacError, aaac_act_stats, aaac_act_stats_workspace, aaac_dequant, aaac_encode, aaac_fit,
+    aaac_fit_batch, aaac_fit_workspace, library, library_path, NVFP4, INT4,
+)
