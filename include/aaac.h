@@ -1,0 +1,131 @@
+/* libaaac — MI355X (gfx950) kernels for the per-layer activation-weighted
+ * k-means of AAAC (Activation-Aware Adaptive Codebooks, 4-bit LLM weight
+ * quantisation): two learned 16-entry scalar codebooks T0, T1 per linear layer,
+ * one of them selected per weight group, the choice stored in the sign bit of the
+ * group's positive scale.
+ *
+ * C ABI.  Conventions common to every entry point:
+ *   - "dev" pointers are HIP device pointers on the current device; "HOST"
+ *     pointers are ordinary host memory, read before the call returns.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no state
+ *     between calls and never synchronises: all work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream); outputs are
+ *     valid once the caller has synchronised that stream.  Two calls may run
+ *     concurrently if they use different workspaces and outputs.
+ *   - bf16 tensors are arrays of 16-bit patterns (upper half of an IEEE fp32).
+ *   - Matrices are row-major with a leading dimension in elements; weight groups
+ *     of `group_size` run along the input dimension K of W [N x K].
+ *   - Return value: AAAC_OK or a negative aaac_status_t.  Arguments are validated
+ *     on the host before any HIP call, so argument errors are reported without a
+ *     GPU; a failed launch gives AAAC_ERR_HIP.  Not checked: that W, X and the
+ *     importances are finite and the importances non-negative.
+ *   - Matrix pointers may be NULL when N == 0 (nothing is read or written).
+ *   - Shapes: K % group_size == 0, group_size in {16, 32, 64, 128}, leading
+ *     dimensions >= K and multiples of 8, device matrices 16-byte aligned.
+ */
+#ifndef AAAC_H_
+#define AAAC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Scale format of a group (paper section 3.1, "a scale s is computed from the
+ * group's weight statistics"; constants are those of the two benchmark settings):
+ *   NVFP4: stored scale = OCP FP8 E4M3 (nearest-even, saturating) of absmax/6, 1 byte
+ *   INT4 : stored scale = bf16 (nearest-even) of absmax/7, 2 bytes
+ * A scale that would be 0 (or, for bf16, subnormal) is replaced by the smallest
+ * positive value (E4M3 0x01 = 2^-9, bf16 0x0080 = 2^-126), so a stored scale is
+ * always > 0 and its top bit is free to carry the selection bit. */
+typedef enum { AAAC_FMT_NVFP4 = 0, AAAC_FMT_INT4 = 1 } aaac_format_t;
+
+typedef enum {
+  AAAC_OK = 0,
+  AAAC_ERR_NULL = -1,      /* a required pointer is NULL */
+  AAAC_ERR_SHAPE = -2,     /* sizes, leading dimensions, group size or alignment */
+  AAAC_ERR_ARG = -3,       /* format, iteration count or initial grid (unsorted / not finite) */
+  AAAC_ERR_WORKSPACE = -4, /* workspace NULL, misaligned (256 B) or too small */
+  AAAC_ERR_HIP = -5        /* a HIP call failed */
+} aaac_status_t;
+
+const char* aaac_status_string(int status);
+
+/* ---- Activation importance (paper Eq. "importance": I_k = sum_t X[t,k]^2;
+ * Alg. 1 step 3).  X: dev bf16 [tokens x ldx].  importance: dev fp32 [K],
+ * overwritten; each entry is the sum taken in fp64 and rounded once to fp32.
+ * tokens == 0 gives zeros.  ws: dev scratch of at least
+ * aaac_act_stats_workspace(tokens, K) bytes, 256-byte aligned. */
+size_t aaac_act_stats_workspace(int64_t tokens, int64_t K);
+int aaac_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- Codebook learning (paper Alg. 1 from "compute scales" to the end of the
+ * outer loop, with n_inner = 1 and caller-supplied initial tables; Eq.
+ * "selection" for the assignment step, Eq. "kmeans_update" for the table update).
+ * One iteration = one assignment step over every group (nearest entry of each
+ * normalised weight w~ = w * fl32(1/s) in T0 and in T1 by the midpoint rule: index
+ * = number of midpoints fl32(0.5*(T[i]+T[i+1])) strictly below w~; per-group errors
+ * sum_k I_k (w~ - T[idx])^2 in fp32, summed as a balanced tree of adjacent pairs;
+ * sigma = 1 iff e1 < e0) followed by one weighted-centroid update of all 32
+ * entries (sums in fp64; an entry whose cell has zero total importance keeps its
+ * value), after which each table is sorted ascending.
+ *   W            dev bf16 [N x ldw]
+ *   importance   dev fp32 [K], >= 0
+ *   init_grid    HOST fp32 [32]: T0[0..15] then T1[0..15], each non-decreasing, finite
+ *   iterations   >= 0 (0 returns the initial grid)
+ *   tables_f32   dev fp32 [32] or NULL: tables after the last update (not rounded);
+ *                feeding them back as init_grid continues the iteration exactly
+ *   tables_bf16  dev u16 [32]: the same rounded to bf16 (nearest-even) — the
+ *                64-byte per-layer artefact (paper section 3.2 "Storage")
+ *   objective_trace dev fp64 [iterations] or NULL: sum over groups of min(e0, e1)
+ *                as seen by each assignment step
+ *   ws           dev scratch, >= aaac_fit_workspace(N, K, group_size, fmt) bytes
+ * N == 0 is allowed (tables stay at init_grid). */
+size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt);
+int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
+             const float* importance, const float* init_grid, int iterations, float* tables_f32,
+             uint16_t* tables_bf16, double* objective_trace, void* ws, size_t ws_bytes,
+             void* hip_stream);
+
+/* Several layers that share group size, format, initial grid and iteration count
+ * (e.g. the seven linears of a decoder block) in one call; per-layer semantics are
+ * exactly those of aaac_fit.  `layers` is a HOST array. */
+typedef struct {
+  const void* W;           /* dev bf16 [N x ldw] */
+  int64_t N, K, ldw;
+  const float* importance; /* dev fp32 [K] */
+  float* tables_f32;       /* dev [32] or NULL */
+  uint16_t* tables_bf16;   /* dev [32] */
+  double* objective_trace; /* dev [iterations] or NULL */
+} aaac_layer_t;
+size_t aaac_fit_batch_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
+                                aaac_format_t fmt);
+int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
+                   const float* init_grid, int iterations, void* ws, size_t ws_bytes,
+                   void* hip_stream);
+
+/* ---- Final encode (paper Alg. 1, last four steps; Eq. "aaac_code").  With the
+ * bf16 tables (each non-decreasing), recompute sigma per group, write each
+ * weight's nearest-entry index into the selected table as a 4-bit code, and the
+ * group's scale with sigma in its top bit.
+ *   tables_bf16  dev u16 [32]
+ *   codes        dev u8 [N x K/2], dense: column k even -> low nibble, odd -> high
+ *   scales       dev [N x K/group_size] of u8 (NVFP4) or u16 (INT4); top bit = sigma */
+int aaac_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
+                const float* importance, const uint16_t* tables_bf16, uint8_t* codes, void* scales,
+                void* hip_stream);
+
+/* ---- Dequantisation (paper Eq. "aaac_dequant"): W_hat[n,k] = bf16( T_sigma[code]
+ * * s ), sigma = top bit of the stored scale, s = the scale with that bit cleared.
+ *   W_hat        dev bf16 [N x ldo] */
+int aaac_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16, int64_t N,
+                 int64_t K, int group_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
+                 void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AAAC_H_ */

@@ -1,0 +1,55 @@
+// Host-side launch interface between the C ABI (aaac_api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace aaac {
+
+constexpr int kStripCols = 512;      // columns covered by one wavefront: 64 lanes x 8 bf16
+constexpr int kPartialStride = 72;   // doubles per block partial: 32 Swx, 32 Sw, objective, pad
+
+struct Grid32 {  // initial tables, passed to a kernel by value
+  float t[32];
+};
+
+// Device-resident state of one layer's fit (lives at the start of its workspace).
+struct FitState {
+  float tables[32];   // current T0[16], T1[16], ascending
+  double objective;   // objective of the latest assignment step
+};
+
+// How a layer is cut into wavefront work units for the Lloyd iteration.
+struct FitPlan {
+  int64_t N, K, ldw;
+  int group_size;
+  int strips;         // ceil(K / 512)
+  int rows_per_unit;  // rows handled by one wavefront
+  int64_t units;      // strips * ceil(N / rows_per_unit)
+  int blocks;         // ceil(units / 4)
+  // workspace layout (byte offsets)
+  size_t off_state, off_rinv, off_partials, bytes;
+};
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size);
+
+struct StatsPlan {
+  int strips;
+  int token_chunks;       // blocks along the token axis
+  int64_t tokens_per_chunk;
+  size_t bytes;
+};
+StatsPlan make_stats_plan(int64_t tokens, int64_t K);
+
+hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                            void* ws, const StatsPlan& plan, hipStream_t stream);
+hipError_t launch_fit(const void* W, const FitPlan& plan, int fmt, const float* importance,
+                      const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
+                      double* objective_trace, void* ws, hipStream_t stream);
+hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
+                         const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
+                         void* scales, hipStream_t stream);
+hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16,
+                          int64_t N, int64_t K, int group_size, int fmt, void* W_hat, int64_t ldo,
+                          hipStream_t stream);
+
+}  // namespace aaac

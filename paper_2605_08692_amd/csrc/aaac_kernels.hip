@@ -1,0 +1,516 @@
+// gfx950 kernels of the AAAC hot path and their launchers.
+//
+// Work mapping used throughout: one lane owns 8 consecutive bf16 weights of a row
+// (one 16-byte load), so a weight group of g = 16..128 is held by g/8 = 2..16
+// adjacent lanes and group reductions are DPP exchanges inside a wavefront.
+// All fp32 arithmetic that decides a code or a selection bit is written as single
+// IEEE operations (the file is compiled with -ffp-contract=off).
+#include "aaac_device.h"
+#include "aaac_internal.h"
+
+namespace aaac {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Index of the nearest entry: number of midpoints strictly below x.
+__device__ __forceinline__ int count_above(float x, const float (&m)[15]) {
+  int idx = 0;
+#pragma unroll
+  for (int i = 0; i < 15; ++i) idx += (x > m[i]) ? 1 : 0;
+  return idx;
+}
+
+__device__ __forceinline__ float tree8(const float (&u)[8]) {
+  return ((u[0] + u[1]) + (u[2] + u[3])) + ((u[4] + u[5]) + (u[6] + u[7]));
+}
+
+__device__ __forceinline__ void load_midpoints(const float* sT, float (&m0)[15], float (&m1)[15]) {
+#pragma unroll
+  for (int i = 0; i < 15; ++i) {
+    m0[i] = 0.5f * (sT[i] + sT[i + 1]);
+    m1[i] = 0.5f * (sT[16 + i] + sT[17 + i]);
+  }
+}
+
+// Assignment of one lane's 8 normalised weights under both tables.
+struct Assign8 {
+  float wn[8];
+  int i0[8], i1[8];
+  float e0, e1;  // group errors (identical in every lane of the group)
+};
+
+template <int LANES>
+__device__ __forceinline__ Assign8 assign8(const W8& x, float r, const float (&Iv)[8], const float* sT,
+                                           const float (&m0)[15], const float (&m1)[15]) {
+  Assign8 a;
+  float u0[8], u1[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    float wn = x.w[p] * r;
+    a.wn[p] = wn;
+    a.i0[p] = count_above(wn, m0);
+    a.i1[p] = count_above(wn, m1);
+    float d0 = wn - sT[a.i0[p]];
+    float d1 = wn - sT[16 + a.i1[p]];
+    float q0 = d0 * d0;
+    float q1 = d1 * d1;
+    u0[p] = Iv[p] * q0;
+    u1[p] = Iv[p] * q1;
+  }
+  a.e0 = group_sum<LANES>(tree8(u0));
+  a.e1 = group_sum<LANES>(tree8(u1));
+  return a;
+}
+
+// Scale of a group from its absmax; returns the unsigned stored code.
+template <int FMT>
+__device__ __forceinline__ uint32_t scale_code(float absmax, float* s) {
+  if (FMT == 0) {
+    uint32_t c = e4m3_rne_sat(div_rn(absmax, 6.0f));
+    c = c == 0u ? 1u : c;
+    *s = e4m3_value(c);
+    return c;
+  }
+  uint32_t c = bf16_rne(div_rn(absmax, 7.0f));
+  c = c < 0x80u ? 0x80u : c;
+  *s = __uint_as_float(c << 16);
+  return c;
+}
+
+// ------------------------------------------------------------ importance
+
+// Partial column sums of squares over one chunk of tokens.  Block = 4 waves on
+// the same 512 columns, wave w takes tokens t0+w, t0+w+4, ...
+__global__ __launch_bounds__(kBlock) void act_stats_partial_kernel(
+    const uint16_t* __restrict__ X, int64_t tokens, int64_t K, int64_t ldx, int64_t tokens_per_chunk,
+    double* __restrict__ partials, int64_t Kpad) {
+  __shared__ double sred[kWavesPerBlock][kStripCols];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t col = (int64_t)blockIdx.x * kStripCols + lane * 8;
+  const int64_t t0 = (int64_t)blockIdx.y * tokens_per_chunk;
+  const int64_t t1 = t0 + tokens_per_chunk < tokens ? t0 + tokens_per_chunk : tokens;
+  double acc[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) acc[p] = 0.0;
+  if (col < K) {
+    const uint16_t* base = X + col;
+#pragma unroll 4
+    for (int64_t t = t0 + wave; t < t1; t += kWavesPerBlock) {
+      W8 x = unpack8(*reinterpret_cast<const uint4*>(base + t * ldx));
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        double v = (double)x.w[p];
+        acc[p] = fma(v, v, acc[p]);
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < 8; ++p) sred[wave][lane * 8 + p] = acc[p];
+  __syncthreads();
+  for (int c = threadIdx.x; c < kStripCols; c += kBlock) {
+    double s = (sred[0][c] + sred[1][c]) + (sred[2][c] + sred[3][c]);
+    partials[(int64_t)blockIdx.y * Kpad + (int64_t)blockIdx.x * kStripCols + c] = s;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void act_stats_reduce_kernel(const double* __restrict__ partials,
+                                                                  int chunks, int64_t K, int64_t Kpad,
+                                                                  float* __restrict__ importance) {
+  const int64_t col = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (col >= K) return;
+  double s = 0.0;
+  for (int c = 0; c < chunks; ++c) s += partials[(int64_t)c * Kpad + col];
+  importance[col] = (float)s;
+}
+
+// ---------------------------------------------------- scales (reciprocals)
+
+template <int LANES, int FMT>
+__global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __restrict__ W, int64_t N,
+                                                            int64_t K, int64_t ldw,
+                                                            float* __restrict__ rinv) {
+  const int64_t cpr = K / 8;  // chunks per row
+  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = c < N * cpr;
+  const int64_t row = active ? c / cpr : 0;
+  const int64_t col = active ? (c % cpr) * 8 : 0;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+  float a = group_max<LANES>(absmax8(unpack8(v)));
+  float s;
+  scale_code<FMT>(a, &s);
+  if (active && (threadIdx.x % LANES) == 0) rinv[row * (K / (8 * LANES)) + col / (8 * LANES)] = div_rn(1.0f, s);
+}
+
+// -------------------------------------------------------- Lloyd iteration
+
+// One fused assignment + accumulation pass.  A wavefront owns a strip of 512
+// columns and a range of rows; its lanes keep their 8 importances in registers.
+// The 32 bins x (sum I*w~, sum I) are accumulated in fp64 in a block-wide LDS
+// histogram with 16 slots per bin, and written out once per block.
+template <int LANES>
+__global__ __launch_bounds__(kBlock) void lloyd_iter_kernel(
+    const uint16_t* __restrict__ W, int64_t N, int64_t K, int64_t ldw, const float* __restrict__ rinv,
+    const float* __restrict__ importance, const FitState* __restrict__ state,
+    double* __restrict__ partials, int strips, int rows_per_unit, int64_t units) {
+  __shared__ float sT[32];
+  __shared__ double hist[64 * 16];
+  __shared__ double sobj[kWavesPerBlock];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 32) sT[tid] = state->tables[tid];
+  for (int i = tid; i < 64 * 16; i += kBlock) hist[i] = 0.0;
+  __syncthreads();
+  float m0[15], m1[15];
+  load_midpoints(sT, m0, m1);
+
+  double obj = 0.0;
+  const int64_t unit = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (unit < units) {
+    const int strip = (int)(unit % strips);
+    const int64_t r0 = (unit / strips) * rows_per_unit;
+    const int64_t r1 = r0 + rows_per_unit < N ? r0 + rows_per_unit : N;
+    const int64_t col = (int64_t)strip * kStripCols + lane * 8;
+    const bool active = col < K;
+    const int64_t G = K / (8 * LANES);
+    const int64_t gidx = col / (8 * LANES);
+    float Iv[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
+    const int slot = lane & 15;
+    for (int64_t row = r0; row < r1; ++row) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      float r = 0.0f;
+      if (active) {
+        v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+        r = rinv[row * G + gidx];
+      }
+      Assign8 a = assign8<LANES>(unpack8(v), r, Iv, sT, m0, m1);
+      const bool sigma = a.e1 < a.e0;
+      if (active) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          int b = sigma ? 16 + a.i1[p] : a.i0[p];
+          atomicAdd(&hist[b * 16 + slot], (double)Iv[p] * (double)a.wn[p]);
+          atomicAdd(&hist[(32 + b) * 16 + slot], (double)Iv[p]);
+        }
+        if ((lane % LANES) == 0) obj += (double)(sigma ? a.e1 : a.e0);
+      }
+    }
+  }
+  // wavefront sum of the objective
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) obj += __shfl_down(obj, off);
+  if (lane == 0) sobj[wave] = obj;
+  __syncthreads();
+  double* out = partials + (int64_t)blockIdx.x * kPartialStride;
+  if (tid < 64) {
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) s += hist[tid * 16 + k];
+    out[tid] = s;
+  } else if (tid == 64) {
+    out[64] = (sobj[0] + sobj[1]) + (sobj[2] + sobj[3]);
+  }
+}
+
+// Reduce the block partials, update the 32 entries, sort, publish.
+constexpr int kFinParts = 14;  // 14 x 72 = 1008 threads
+__global__ __launch_bounds__(kFinParts* kPartialStride) void finalise_kernel(
+    const double* __restrict__ partials, int blocks, FitState* __restrict__ state,
+    double* __restrict__ objective_trace, int iteration) {
+  __shared__ double red[kFinParts][kPartialStride];
+  __shared__ double sums[kPartialStride];
+  __shared__ float sT[32];
+  const int tid = threadIdx.x, b = tid % kPartialStride, part = tid / kPartialStride;
+  double s = 0.0;
+  if (b <= 64)
+    for (int i = part; i < blocks; i += kFinParts) s += partials[(int64_t)i * kPartialStride + b];
+  red[part][b] = s;
+  __syncthreads();
+  if (tid < kPartialStride) {
+    double t = 0.0;
+#pragma unroll
+    for (int p = 0; p < kFinParts; ++p) t += red[p][tid];
+    sums[tid] = t;
+  }
+  __syncthreads();
+  if (tid < 32) {
+    double den = sums[32 + tid];
+    float old = state->tables[tid];
+    sT[tid] = den > 0.0 ? (float)(sums[tid] / den) : old;
+  }
+  __syncthreads();
+  if (tid < 2) {  // stable insertion sort of one table
+    float* T = sT + 16 * tid;
+    for (int i = 1; i < 16; ++i) {
+      float v = T[i];
+      int j = i - 1;
+      while (j >= 0 && T[j] > v) { T[j + 1] = T[j]; --j; }
+      T[j + 1] = v;
+    }
+  }
+  __syncthreads();
+  if (tid < 32) state->tables[tid] = sT[tid];
+  if (tid == 32) {
+    state->objective = sums[64];
+    if (objective_trace) objective_trace[iteration] = sums[64];
+  }
+}
+
+__global__ void init_state_kernel(Grid32 grid, FitState* state) {
+  if (threadIdx.x < 32) state->tables[threadIdx.x] = grid.t[threadIdx.x];
+  if (threadIdx.x == 32) state->objective = 0.0;
+}
+
+__global__ void export_tables_kernel(const FitState* state, float* tables_f32, uint16_t* tables_bf16) {
+  if (threadIdx.x < 32) {
+    float t = state->tables[threadIdx.x];
+    if (tables_f32) tables_f32[threadIdx.x] = t;
+    tables_bf16[threadIdx.x] = (uint16_t)bf16_rne(t);
+  }
+}
+
+// ----------------------------------------------------------------- encode
+
+template <int LANES, int FMT>
+__global__ __launch_bounds__(kBlock) void encode_kernel(
+    const uint16_t* __restrict__ W, int64_t N, int64_t K, int64_t ldw,
+    const float* __restrict__ importance, const uint16_t* __restrict__ tables_bf16,
+    uint8_t* __restrict__ codes, void* __restrict__ scales) {
+  __shared__ float sT[32];
+  if (threadIdx.x < 32) sT[threadIdx.x] = __uint_as_float((uint32_t)tables_bf16[threadIdx.x] << 16);
+  __syncthreads();
+  float m0[15], m1[15];
+  load_midpoints(sT, m0, m1);
+  const int64_t cpr = K / 8;
+  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = c < N * cpr;
+  const int64_t row = active ? c / cpr : 0;
+  const int64_t col = active ? (c % cpr) * 8 : 0;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  float Iv[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
+  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+  W8 x = unpack8(v);
+  float s;
+  uint32_t sc = scale_code<FMT>(group_max<LANES>(absmax8(x)), &s);
+  float r = div_rn(1.0f, s);
+  Assign8 a = assign8<LANES>(x, r, Iv, sT, m0, m1);
+  const bool sigma = a.e1 < a.e0;
+  if (!active) return;
+  uint32_t packed = 0;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) packed |= (uint32_t)(sigma ? a.i1[p] : a.i0[p]) << (4 * p);
+  *reinterpret_cast<uint32_t*>(codes + (row * K + col) / 2) = packed;
+  if ((threadIdx.x % LANES) == 0) {
+    const int64_t g = row * (K / (8 * LANES)) + col / (8 * LANES);
+    if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sigma ? 0x80u : 0u));
+    else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sigma ? 0x8000u : 0u));
+  }
+}
+
+// ---------------------------------------------------------------- dequant
+
+template <int FMT>
+__global__ __launch_bounds__(kBlock) void dequant_kernel(
+    const uint8_t* __restrict__ codes, const void* __restrict__ scales,
+    const uint16_t* __restrict__ tables_bf16, int64_t N, int64_t K, int group_size,
+    uint16_t* __restrict__ W_hat, int64_t ldo) {
+  __shared__ float sT[32];
+  if (threadIdx.x < 32) sT[threadIdx.x] = __uint_as_float((uint32_t)tables_bf16[threadIdx.x] << 16);
+  __syncthreads();
+  const int64_t cpr = K / 8;
+  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (c >= N * cpr) return;
+  const int64_t row = c / cpr, col = (c % cpr) * 8;
+  const int64_t g = row * (K / group_size) + col / group_size;
+  uint32_t sc, sigma;
+  float s;
+  if (FMT == 0) {
+    sc = static_cast<const uint8_t*>(scales)[g];
+    sigma = sc >> 7;
+    s = e4m3_value(sc & 0x7Fu);
+  } else {
+    sc = static_cast<const uint16_t*>(scales)[g];
+    sigma = sc >> 15;
+    s = __uint_as_float((sc & 0x7FFFu) << 16);
+  }
+  const uint32_t packed = *reinterpret_cast<const uint32_t*>(codes + (row * K + col) / 2);
+  const float* T = sT + 16 * sigma;
+  uint32_t h[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) h[p] = bf16_rne(T[(packed >> (4 * p)) & 15u] * s);
+  uint4 out = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+  *reinterpret_cast<uint4*>(W_hat + row * ldo + col) = out;
+}
+
+// Plain fill, used instead of a memset node so that callers may capture the
+// stream into a graph.
+__global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t stream) {  // bytes % 4 == 0
+  const int64_t n = (int64_t)(bytes / 4);
+  if (n == 0) return hipSuccess;
+  fill_zero_kernel<<<(unsigned)ceil_div(n, kBlock), kBlock, 0, stream>>>(static_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- plans
+
+StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
+  StatsPlan p;
+  p.strips = (int)ceil_div(K, kStripCols);
+  int64_t want = ceil_div(2048, p.strips);           // about 8 blocks per CU in total
+  int64_t most = ceil_div(tokens > 0 ? tokens : 1, 64);  // at least 16 tokens per wavefront
+  int64_t chunks = want < most ? want : most;
+  if (chunks < 1) chunks = 1;
+  if (chunks > 65535) chunks = 65535;
+  p.tokens_per_chunk = ceil_div(ceil_div(tokens > 0 ? tokens : 1, chunks), 4) * 4;
+  p.token_chunks = (int)ceil_div(tokens > 0 ? tokens : 1, p.tokens_per_chunk);
+  p.bytes = (size_t)p.token_chunks * p.strips * kStripCols * sizeof(double);
+  return p;
+}
+
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
+  FitPlan p;
+  p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size;
+  p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
+  int64_t row_strips = (N > 0 ? N : 1) * p.strips;
+  p.rows_per_unit = (int)ceil_div(row_strips, 4096);  // about 16 wavefronts per CU in total
+  if (p.rows_per_unit < 1) p.rows_per_unit = 1;
+  p.units = p.strips * ceil_div(N > 0 ? N : 1, p.rows_per_unit);
+  p.blocks = (int)ceil_div(p.units, kWavesPerBlock);
+  auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  p.off_state = 0;
+  p.off_rinv = align(sizeof(FitState));
+  p.off_partials = p.off_rinv + align((size_t)(N > 0 ? N : 0) * (K / group_size) * sizeof(float));
+  p.bytes = p.off_partials + align((size_t)p.blocks * kPartialStride * sizeof(double));
+  return p;
+}
+
+// -------------------------------------------------------------- launchers
+
+#define AAAC_LAUNCH_CHECK()                     \
+  do {                                          \
+    hipError_t e_ = hipGetLastError();          \
+    if (e_ != hipSuccess) return e_;            \
+  } while (0)
+
+hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                            void* ws, const StatsPlan& plan, hipStream_t stream) {
+  const int64_t Kpad = (int64_t)plan.strips * kStripCols;
+  double* partials = static_cast<double*>(ws);
+  if (tokens == 0) {
+    return fill_zero(importance, (size_t)K * sizeof(float), stream);
+  }
+  act_stats_partial_kernel<<<dim3(plan.strips, plan.token_chunks), kBlock, 0, stream>>>(
+      static_cast<const uint16_t*>(X), tokens, K, ldx, plan.tokens_per_chunk, partials, Kpad);
+  AAAC_LAUNCH_CHECK();
+  act_stats_reduce_kernel<<<(unsigned)ceil_div(K, kBlock), kBlock, 0, stream>>>(partials, plan.token_chunks,
+                                                                                 K, Kpad, importance);
+  AAAC_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+template <int LANES>
+static hipError_t launch_fit_lanes(const uint16_t* W, const FitPlan& p, int fmt, const float* importance,
+                                   int iterations, FitState* state, float* rinv, double* partials,
+                                   double* objective_trace, hipStream_t stream) {
+  const int64_t chunks = p.N * (p.K / 8);
+  const unsigned gblocks = (unsigned)ceil_div(chunks, kBlock);
+  if (fmt == 0)
+    group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv);
+  else
+    group_rinv_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv);
+  AAAC_LAUNCH_CHECK();
+  for (int it = 0; it < iterations; ++it) {
+    lloyd_iter_kernel<LANES><<<p.blocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv, importance, state,
+                                                             partials, p.strips, p.rows_per_unit, p.units);
+    AAAC_LAUNCH_CHECK();
+    finalise_kernel<<<1, kFinParts * kPartialStride, 0, stream>>>(partials, p.blocks, state,
+                                                                 objective_trace, it);
+    AAAC_LAUNCH_CHECK();
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_fit(const void* W, const FitPlan& p, int fmt, const float* importance,
+                      const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
+                      double* objective_trace, void* ws, hipStream_t stream) {
+  char* base = static_cast<char*>(ws);
+  FitState* state = reinterpret_cast<FitState*>(base + p.off_state);
+  float* rinv = reinterpret_cast<float*>(base + p.off_rinv);
+  double* partials = reinterpret_cast<double*>(base + p.off_partials);
+  init_state_kernel<<<1, 64, 0, stream>>>(grid, state);
+  AAAC_LAUNCH_CHECK();
+  if (p.N > 0 && p.K > 0 && iterations > 0) {
+    const uint16_t* Wp = static_cast<const uint16_t*>(W);
+    hipError_t e = hipSuccess;
+    switch (p.group_size / 8) {
+      case 2: e = launch_fit_lanes<2>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
+      case 4: e = launch_fit_lanes<4>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
+      case 8: e = launch_fit_lanes<8>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
+      default: e = launch_fit_lanes<16>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
+    }
+    if (e != hipSuccess) return e;
+  } else if (objective_trace && iterations > 0) {
+    hipError_t e = fill_zero(objective_trace, sizeof(double) * iterations, stream);
+    if (e != hipSuccess) return e;
+  }
+  export_tables_kernel<<<1, 64, 0, stream>>>(state, tables_f32, tables_bf16);
+  AAAC_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+template <int LANES>
+static hipError_t launch_encode_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt,
+                                      const float* importance, const uint16_t* tables_bf16,
+                                      uint8_t* codes, void* scales, hipStream_t stream) {
+  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  if (fmt == 0)
+    encode_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, importance, tables_bf16, codes, scales);
+  else
+    encode_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, importance, tables_bf16, codes, scales);
+  AAAC_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
+                         const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
+                         void* scales, hipStream_t stream) {
+  if (N == 0 || K == 0) return hipSuccess;
+  const uint16_t* Wp = static_cast<const uint16_t*>(W);
+  switch (group_size / 8) {
+    case 2: return launch_encode_lanes<2>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
+    case 4: return launch_encode_lanes<4>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
+    case 8: return launch_encode_lanes<8>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
+    default: return launch_encode_lanes<16>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
+  }
+}
+
+hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16,
+                          int64_t N, int64_t K, int group_size, int fmt, void* W_hat, int64_t ldo,
+                          hipStream_t stream) {
+  if (N == 0 || K == 0) return hipSuccess;
+  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  uint16_t* out = static_cast<uint16_t*>(W_hat);
+  if (fmt == 0)
+    dequant_kernel<0><<<gblocks, kBlock, 0, stream>>>(codes, scales, tables_bf16, N, K, group_size, out, ldo);
+  else
+    dequant_kernel<1><<<gblocks, kBlock, 0, stream>>>(codes, scales, tables_bf16, N, K, group_size, out, ldo);
+  AAAC_LAUNCH_CHECK();
+  return hipSuccess;
+}
+
+}  // namespace aaac
