@@ -15,8 +15,7 @@ struct Grid32 {  // initial tables, passed to a kernel by value
 
 // Device-resident state of one layer's fit (lives at the start of its workspace).
 struct FitState {
-  float tables[32];   // current T0[16], T1[16], ascending
-  double objective;   // objective of the latest assignment step
+  float tables[2][32];  // T0[16], T1[16] of iteration t at [t & 1], ascending
 };
 
 // How a layer is cut into wavefront work units for the Lloyd iteration.
@@ -26,7 +25,7 @@ struct FitPlan {
   int strips;         // ceil(K / 512)
   int rows_per_unit;  // rows handled by one wavefront
   int64_t units;      // strips * ceil(N / rows_per_unit)
-  int blocks;         // ceil(units / 4)
+  int blocks;         // ceil(units / 16)
   // workspace layout (byte offsets)
   size_t off_state, off_rinv, off_partials, bytes;
 };
@@ -45,6 +44,9 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
 hipError_t launch_fit(const void* W, const FitPlan& plan, int fmt, const float* importance,
                       const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
                       double* objective_trace, void* ws, hipStream_t stream);
+hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
+                             float* rinv, hipStream_t stream);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
                          const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
                          void* scales, hipStream_t stream);

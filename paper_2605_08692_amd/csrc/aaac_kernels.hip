@@ -4,7 +4,9 @@
 // (one 16-byte load), so a weight group of g = 16..128 is held by g/8 = 2..16
 // adjacent lanes and group reductions are DPP exchanges inside a wavefront.
 // All fp32 arithmetic that decides a code or a selection bit is written as single
-// IEEE operations (the file is compiled with -ffp-contract=off).
+// IEEE operations (the file is compiled with -ffp-contract=off).  This file holds
+// the importance, scale, encode and dequant kernels; the Lloyd iteration is in
+// aaac_lloyd.hip.
 #include "aaac_device.h"
 #include "aaac_internal.h"
 
@@ -145,134 +147,6 @@ __global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __re
   if (active && (threadIdx.x % LANES) == 0) rinv[row * (K / (8 * LANES)) + col / (8 * LANES)] = div_rn(1.0f, s);
 }
 
-// -------------------------------------------------------- Lloyd iteration
-
-// One fused assignment + accumulation pass.  A wavefront owns a strip of 512
-// columns and a range of rows; its lanes keep their 8 importances in registers.
-// The 32 bins x (sum I*w~, sum I) are accumulated in fp64 in a block-wide LDS
-// histogram with 16 slots per bin, and written out once per block.
-template <int LANES>
-__global__ __launch_bounds__(kBlock) void lloyd_iter_kernel(
-    const uint16_t* __restrict__ W, int64_t N, int64_t K, int64_t ldw, const float* __restrict__ rinv,
-    const float* __restrict__ importance, const FitState* __restrict__ state,
-    double* __restrict__ partials, int strips, int rows_per_unit, int64_t units) {
-  __shared__ float sT[32];
-  __shared__ double hist[64 * 16];
-  __shared__ double sobj[kWavesPerBlock];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid < 32) sT[tid] = state->tables[tid];
-  for (int i = tid; i < 64 * 16; i += kBlock) hist[i] = 0.0;
-  __syncthreads();
-  float m0[15], m1[15];
-  load_midpoints(sT, m0, m1);
-
-  double obj = 0.0;
-  const int64_t unit = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (unit < units) {
-    const int strip = (int)(unit % strips);
-    const int64_t r0 = (unit / strips) * rows_per_unit;
-    const int64_t r1 = r0 + rows_per_unit < N ? r0 + rows_per_unit : N;
-    const int64_t col = (int64_t)strip * kStripCols + lane * 8;
-    const bool active = col < K;
-    const int64_t G = K / (8 * LANES);
-    const int64_t gidx = col / (8 * LANES);
-    float Iv[8];
-#pragma unroll
-    for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
-    const int slot = lane & 15;
-    for (int64_t row = r0; row < r1; ++row) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      float r = 0.0f;
-      if (active) {
-        v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
-        r = rinv[row * G + gidx];
-      }
-      Assign8 a = assign8<LANES>(unpack8(v), r, Iv, sT, m0, m1);
-      const bool sigma = a.e1 < a.e0;
-      if (active) {
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          int b = sigma ? 16 + a.i1[p] : a.i0[p];
-          atomicAdd(&hist[b * 16 + slot], (double)Iv[p] * (double)a.wn[p]);
-          atomicAdd(&hist[(32 + b) * 16 + slot], (double)Iv[p]);
-        }
-        if ((lane % LANES) == 0) obj += (double)(sigma ? a.e1 : a.e0);
-      }
-    }
-  }
-  // wavefront sum of the objective
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) obj += __shfl_down(obj, off);
-  if (lane == 0) sobj[wave] = obj;
-  __syncthreads();
-  double* out = partials + (int64_t)blockIdx.x * kPartialStride;
-  if (tid < 64) {
-    double s = 0.0;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) s += hist[tid * 16 + k];
-    out[tid] = s;
-  } else if (tid == 64) {
-    out[64] = (sobj[0] + sobj[1]) + (sobj[2] + sobj[3]);
-  }
-}
-
-// Reduce the block partials, update the 32 entries, sort, publish.
-constexpr int kFinParts = 14;  // 14 x 72 = 1008 threads
-__global__ __launch_bounds__(kFinParts* kPartialStride) void finalise_kernel(
-    const double* __restrict__ partials, int blocks, FitState* __restrict__ state,
-    double* __restrict__ objective_trace, int iteration) {
-  __shared__ double red[kFinParts][kPartialStride];
-  __shared__ double sums[kPartialStride];
-  __shared__ float sT[32];
-  const int tid = threadIdx.x, b = tid % kPartialStride, part = tid / kPartialStride;
-  double s = 0.0;
-  if (b <= 64)
-    for (int i = part; i < blocks; i += kFinParts) s += partials[(int64_t)i * kPartialStride + b];
-  red[part][b] = s;
-  __syncthreads();
-  if (tid < kPartialStride) {
-    double t = 0.0;
-#pragma unroll
-    for (int p = 0; p < kFinParts; ++p) t += red[p][tid];
-    sums[tid] = t;
-  }
-  __syncthreads();
-  if (tid < 32) {
-    double den = sums[32 + tid];
-    float old = state->tables[tid];
-    sT[tid] = den > 0.0 ? (float)(sums[tid] / den) : old;
-  }
-  __syncthreads();
-  if (tid < 2) {  // stable insertion sort of one table
-    float* T = sT + 16 * tid;
-    for (int i = 1; i < 16; ++i) {
-      float v = T[i];
-      int j = i - 1;
-      while (j >= 0 && T[j] > v) { T[j + 1] = T[j]; --j; }
-      T[j + 1] = v;
-    }
-  }
-  __syncthreads();
-  if (tid < 32) state->tables[tid] = sT[tid];
-  if (tid == 32) {
-    state->objective = sums[64];
-    if (objective_trace) objective_trace[iteration] = sums[64];
-  }
-}
-
-__global__ void init_state_kernel(Grid32 grid, FitState* state) {
-  if (threadIdx.x < 32) state->tables[threadIdx.x] = grid.t[threadIdx.x];
-  if (threadIdx.x == 32) state->objective = 0.0;
-}
-
-__global__ void export_tables_kernel(const FitState* state, float* tables_f32, uint16_t* tables_bf16) {
-  if (threadIdx.x < 32) {
-    float t = state->tables[threadIdx.x];
-    if (tables_f32) tables_f32[threadIdx.x] = t;
-    tables_bf16[threadIdx.x] = (uint16_t)bf16_rne(t);
-  }
-}
-
 // ----------------------------------------------------------------- encode
 
 template <int LANES, int FMT>
@@ -382,23 +256,6 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
   return p;
 }
 
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
-  FitPlan p;
-  p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size;
-  p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
-  int64_t row_strips = (N > 0 ? N : 1) * p.strips;
-  p.rows_per_unit = (int)ceil_div(row_strips, 4096);  // about 16 wavefronts per CU in total
-  if (p.rows_per_unit < 1) p.rows_per_unit = 1;
-  p.units = p.strips * ceil_div(N > 0 ? N : 1, p.rows_per_unit);
-  p.blocks = (int)ceil_div(p.units, kWavesPerBlock);
-  auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p.off_state = 0;
-  p.off_rinv = align(sizeof(FitState));
-  p.off_partials = p.off_rinv + align((size_t)(N > 0 ? N : 0) * (K / group_size) * sizeof(float));
-  p.bytes = p.off_partials + align((size_t)p.blocks * kPartialStride * sizeof(double));
-  return p;
-}
-
 // -------------------------------------------------------------- launchers
 
 #define AAAC_LAUNCH_CHECK()                     \
@@ -424,54 +281,30 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
 }
 
 template <int LANES>
-static hipError_t launch_fit_lanes(const uint16_t* W, const FitPlan& p, int fmt, const float* importance,
-                                   int iterations, FitState* state, float* rinv, double* partials,
-                                   double* objective_trace, hipStream_t stream) {
-  const int64_t chunks = p.N * (p.K / 8);
-  const unsigned gblocks = (unsigned)ceil_div(chunks, kBlock);
+static hipError_t launch_rinv_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt, float* rinv,
+                                    hipStream_t stream) {
+  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
   if (fmt == 0)
-    group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv);
+    group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   else
-    group_rinv_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv);
+    group_rinv_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   AAAC_LAUNCH_CHECK();
-  for (int it = 0; it < iterations; ++it) {
-    lloyd_iter_kernel<LANES><<<p.blocks, kBlock, 0, stream>>>(W, p.N, p.K, p.ldw, rinv, importance, state,
-                                                             partials, p.strips, p.rows_per_unit, p.units);
-    AAAC_LAUNCH_CHECK();
-    finalise_kernel<<<1, kFinParts * kPartialStride, 0, stream>>>(partials, p.blocks, state,
-                                                                 objective_trace, it);
-    AAAC_LAUNCH_CHECK();
-  }
   return hipSuccess;
 }
 
-hipError_t launch_fit(const void* W, const FitPlan& p, int fmt, const float* importance,
-                      const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
-                      double* objective_trace, void* ws, hipStream_t stream) {
-  char* base = static_cast<char*>(ws);
-  FitState* state = reinterpret_cast<FitState*>(base + p.off_state);
-  float* rinv = reinterpret_cast<float*>(base + p.off_rinv);
-  double* partials = reinterpret_cast<double*>(base + p.off_partials);
-  init_state_kernel<<<1, 64, 0, stream>>>(grid, state);
-  AAAC_LAUNCH_CHECK();
-  if (p.N > 0 && p.K > 0 && iterations > 0) {
-    const uint16_t* Wp = static_cast<const uint16_t*>(W);
-    hipError_t e = hipSuccess;
-    switch (p.group_size / 8) {
-      case 2: e = launch_fit_lanes<2>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
-      case 4: e = launch_fit_lanes<4>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
-      case 8: e = launch_fit_lanes<8>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
-      default: e = launch_fit_lanes<16>(Wp, p, fmt, importance, iterations, state, rinv, partials, objective_trace, stream); break;
-    }
-    if (e != hipSuccess) return e;
-  } else if (objective_trace && iterations > 0) {
-    hipError_t e = fill_zero(objective_trace, sizeof(double) * iterations, stream);
-    if (e != hipSuccess) return e;
+hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
+                             float* rinv, hipStream_t stream) {
+  if (N == 0 || K == 0) return hipSuccess;
+  const uint16_t* Wp = static_cast<const uint16_t*>(W);
+  switch (group_size / 8) {
+    case 2: return launch_rinv_lanes<2>(Wp, N, K, ldw, fmt, rinv, stream);
+    case 4: return launch_rinv_lanes<4>(Wp, N, K, ldw, fmt, rinv, stream);
+    case 8: return launch_rinv_lanes<8>(Wp, N, K, ldw, fmt, rinv, stream);
+    default: return launch_rinv_lanes<16>(Wp, N, K, ldw, fmt, rinv, stream);
   }
-  export_tables_kernel<<<1, 64, 0, stream>>>(state, tables_f32, tables_bf16);
-  AAAC_LAUNCH_CHECK();
-  return hipSuccess;
 }
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) { return fill_zero(p, bytes, stream); }
 
 template <int LANES>
 static hipError_t launch_encode_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt,
