@@ -14,7 +14,7 @@ SOURCES = ["aaac_api.hip", "aaac_kernels.hip", "aaac_lloyd.hip"]
 
 # -ffp-contract=off: every fp32 operation that decides a code or a selection bit
 # must stay a single IEEE operation.  Packed fp32 instructions are switched off.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
 

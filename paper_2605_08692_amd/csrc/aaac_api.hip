@@ -18,7 +18,7 @@ int check_matrix(const void* p, int64_t N, int64_t K, int64_t ld, int group_size
   if (!valid_group(group_size)) return AAAC_ERR_SHAPE;
   if (K % group_size != 0) return AAAC_ERR_SHAPE;
   if (ld < K || ld % 8 != 0) return AAAC_ERR_SHAPE;
-  if (N > (int64_t)1 << 31 || K > (int64_t)1 << 31) return AAAC_ERR_SHAPE;
+  if (N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31) return AAAC_ERR_SHAPE;
   if (!aligned(p, 16)) return AAAC_ERR_SHAPE;
   return AAAC_OK;
 }

@@ -7,7 +7,7 @@
 namespace aaac {
 
 constexpr int kStripCols = 512;      // columns covered by one wavefront: 64 lanes x 8 bf16
-constexpr int kPartialStride = 72;   // doubles per block partial: 32 Swx, 32 Sw, objective, pad
+constexpr int kAccStride = 72;       // doubles per accumulator: 32 sum I*x, 32 sum I, objective, pad
 
 struct Grid32 {  // initial tables, passed to a kernel by value
   float t[32];
@@ -15,7 +15,8 @@ struct Grid32 {  // initial tables, passed to a kernel by value
 
 // Device-resident state of one layer's fit (lives at the start of its workspace).
 struct FitState {
-  float tables[2][32];  // T0[16], T1[16] of iteration t at [t & 1], ascending
+  float tables[2][32];        // T0[16], T1[16] of iteration t at [t & 1], ascending
+  double acc[3][kAccStride];  // sums of iteration t at [t % 3]
 };
 
 // How a layer is cut into wavefront work units for the Lloyd iteration.
@@ -27,7 +28,7 @@ struct FitPlan {
   int64_t units;      // strips * ceil(N / rows_per_unit)
   int blocks;         // ceil(units / 16)
   // workspace layout (byte offsets)
-  size_t off_state, off_rinv, off_partials, bytes;
+  size_t off_state, off_rinv, bytes;
 };
 FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size);
 
