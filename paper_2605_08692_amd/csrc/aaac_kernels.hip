@@ -85,7 +85,8 @@ __device__ __forceinline__ uint32_t scale_code(float absmax, float* s) {
 // ------------------------------------------------------------ importance
 
 // Partial column sums of squares over one chunk of tokens.  Block = 4 waves on
-// the same 512 columns, wave w takes tokens t0+w, t0+w+4, ...
+// the same 512 columns, wave w takes tokens t0+w, t0+w+4, ...; eight 16-byte
+// loads are in flight per lane.  X is read once, so the loads are non-temporal.
 __global__ __launch_bounds__(kBlock) void act_stats_partial_kernel(
     const uint16_t* __restrict__ X, int64_t tokens, int64_t K, int64_t ldx, int64_t tokens_per_chunk,
     double* __restrict__ partials, int64_t Kpad) {
@@ -98,14 +99,25 @@ __global__ __launch_bounds__(kBlock) void act_stats_partial_kernel(
 #pragma unroll
   for (int p = 0; p < 8; ++p) acc[p] = 0.0;
   if (col < K) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const uint16_t* base = X + col;
-#pragma unroll 4
-    for (int64_t t = t0 + wave; t < t1; t += kWavesPerBlock) {
-      W8 x = unpack8(*reinterpret_cast<const uint4*>(base + t * ldx));
+    constexpr int kInFlight = 8;
+    for (int64_t t = t0 + wave; t < t1; t += kWavesPerBlock * kInFlight) {
+      u32x4 v[kInFlight];
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        double v = (double)x.w[p];
-        acc[p] = fma(v, v, acc[p]);
+      for (int u = 0; u < kInFlight; ++u) {
+        const int64_t tu = t + (int64_t)u * kWavesPerBlock;
+        v[u] = u32x4{0u, 0u, 0u, 0u};
+        if (tu < t1) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + tu * ldx));
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        W8 x = unpack8(make_uint4(v[u].x, v[u].y, v[u].z, v[u].w));
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          double d = (double)x.w[p];
+          acc[p] = fma(d, d, acc[p]);
+        }
       }
     }
   }
@@ -118,14 +130,35 @@ __global__ __launch_bounds__(kBlock) void act_stats_partial_kernel(
   }
 }
 
+// Sum of the chunk partials of each column, in a fixed order: block = 16
+// columns x 16 parts, part q adds chunks q, q+16, ..., then the parts are added.
 __global__ __launch_bounds__(kBlock) void act_stats_reduce_kernel(const double* __restrict__ partials,
                                                                   int chunks, int64_t K, int64_t Kpad,
                                                                   float* __restrict__ importance) {
-  const int64_t col = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (col >= K) return;
+  __shared__ double sred[16][16];
+  const int c16 = threadIdx.x & 15, part = threadIdx.x >> 4;
+  const int64_t col = (int64_t)blockIdx.x * 16 + c16;
   double s = 0.0;
-  for (int c = 0; c < chunks; ++c) s += partials[(int64_t)c * Kpad + col];
-  importance[col] = (float)s;
+  if (col < K) {
+    for (int c0 = part; c0 < chunks; c0 += 16 * 8) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int c = c0 + 16 * u;
+        v[u] = c < chunks ? partials[(int64_t)c * Kpad + col] : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+  }
+  sred[part][c16] = s;
+  __syncthreads();
+  if (threadIdx.x < 16 && col < K) {
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t += sred[q][threadIdx.x];
+    importance[col] = (float)t;
+  }
 }
 
 // ---------------------------------------------------- scales (reciprocals)
@@ -274,7 +307,7 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
   act_stats_partial_kernel<<<dim3(plan.strips, plan.token_chunks), kBlock, 0, stream>>>(
       static_cast<const uint16_t*>(X), tokens, K, ldx, plan.tokens_per_chunk, partials, Kpad);
   AAAC_LAUNCH_CHECK();
-  act_stats_reduce_kernel<<<(unsigned)ceil_div(K, kBlock), kBlock, 0, stream>>>(partials, plan.token_chunks,
+  act_stats_reduce_kernel<<<(unsigned)ceil_div(K, 16), kBlock, 0, stream>>>(partials, plan.token_chunks,
                                                                                  K, Kpad, importance);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
