@@ -156,12 +156,42 @@ __device__ __forceinline__ void assign_slow(const float (&Iv)[8], const LloydLds
   a.p1 = tree8(u1);
 }
 
-// Fills the search rows, the bucket table and clears the histogram, from the
-// current tables in sm.newtab.  All threads of the block call it.
-__device__ void build_search_tables(LloydLds& sm) {
-  const int tid = threadIdx.x;
-  if (tid < 40) {
-    const int r = tid / 20, i = tid % 20;
+// Tables of an iteration, computed by ONE wavefront (all 64 lanes call it, no
+// block barrier inside): from the accumulated sums of the previous iteration
+// (acc[0..31] = sum I*x, acc[32..63] = sum I, acc[64] = objective) divide, keep
+// entries whose cell was empty, sort each table (stable); with acc == nullptr the
+// old tables are taken as they are.  Leaves the tables in sm.newtab, the
+// objective in sm.sums[64], and fills the search rows, the bucket map parameters
+// and the bucket of every midpoint.  Lanes of one wavefront run in lockstep and
+// LDS accesses of a wavefront complete in order, so its stores are visible to
+// its own later loads; wave_barrier() only keeps the compiler from reordering.
+__device__ void wave_make_tables(LloydLds& sm, const double* __restrict__ acc,
+                                 const float* __restrict__ old_tables) {
+  const int lane = threadIdx.x & 63;
+  if (lane < 32) {
+    float t = old_tables[lane];
+    if (acc != nullptr) {
+      const double num = acc[lane], den = acc[32 + lane];
+      if (lane == 0) sm.sums[64] = acc[64];
+      if (den > 0.0) t = (float)(num / den);
+    }
+    sm.cand[lane] = t;
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 32) {  // stable rank sort inside each table
+    const int base = lane & 16, i = lane & 15;
+    const float v = sm.cand[lane];
+    int rank = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float u = sm.cand[base + j];
+      rank += (u < v || (u == v && j < i)) ? 1 : 0;
+    }
+    sm.newtab[base + rank] = v;
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 40) {
+    const int r = lane / 20, i = lane % 20;
     const float* T = sm.newtab + 16 * r;
     SearchRow s;
     s.thr = i < 15 ? 0.5f * (T[i] + T[i + 1]) : __builtin_inff();
@@ -170,21 +200,26 @@ __device__ void build_search_tables(LloydLds& sm) {
     s.bin = (uint32_t)(16 * r + (i < 16 ? i : 0)) * (kSlots * 8u);
     sm.row[r][i] = s;
   }
-  __syncthreads();
-  if (tid < 32) {
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 32) {
     const float lo = fminf(sm.row[0][0].thr, sm.row[1][0].thr);
     const float hi = fmaxf(sm.row[0][14].thr, sm.row[1][14].thr);
     const float range = fmaxf(hi - lo, 1e-20f);
     const float inv = (128.0f * (kBuckets - 2)) / range;  // buckets 1..254 span [lo, hi]
     const float off = (128.0f - lo * inv) + 8388608.0f;
-    if (tid == 0) {
+    if (lane == 0) {
       sm.lutpar[0] = inv;
       sm.lutpar[1] = off;
     }
-    const int r = tid >> 4, j = tid & 15;
+    const int r = lane >> 4, j = lane & 15;
     sm.mid_bucket[r][j] = j < 15 ? (int)(bucket_row(sm.row[r][j].thr, inv, off) >> 7) : kBuckets;
   }
-  __syncthreads();
+}
+
+// Bucket table from the midpoint buckets, replicated; all threads of the block
+// call it after wave_make_tables() and a barrier.  Ends with a barrier.
+__device__ void build_bucket_table(LloydLds& sm) {
+  const int tid = threadIdx.x;
   if (tid < kBuckets) {
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
@@ -205,36 +240,6 @@ __device__ void build_search_tables(LloydLds& sm) {
     sm.lut[0][b * kReplicas + (tid % kReplicas)] = sm.entry[0][b];
     sm.lut[1][b * kReplicas + (tid % kReplicas)] = sm.entry[1][b];
   }
-  for (int i = tid; i < 2 * 32 * kSlots; i += kLloydBlock) (&sm.hist[0][0][0])[i] = 0.0;
-  __syncthreads();
-}
-
-// Table update from the accumulated sums of one iteration (acc[0..31] = sum I*x,
-// acc[32..63] = sum I, acc[64] = objective): divide, keep entries whose cell was
-// empty, sort each table (stable).  The result is left in sm.newtab and the
-// objective in sm.sums[64].  All threads of the block call it.
-__device__ void update_tables(LloydLds& sm, const double* __restrict__ acc, const float* __restrict__ old_tables) {
-  const int tid = threadIdx.x;
-  if (tid <= 64) sm.sums[tid] = acc[tid];
-  float old = 0.0f;
-  if (tid < 32) old = old_tables[tid];
-  __syncthreads();
-  if (tid < 32) {
-    const double den = sm.sums[32 + tid];
-    sm.cand[tid] = den > 0.0 ? (float)(sm.sums[tid] / den) : old;
-  }
-  __syncthreads();
-  if (tid < 32) {  // stable rank sort inside each table
-    const int base = tid & 16, i = tid & 15;
-    const float v = sm.cand[tid];
-    int rank = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const float u = sm.cand[base + j];
-      rank += (u < v || (u == v && j < i)) ? 1 : 0;
-    }
-    sm.newtab[base + rank] = v;
-  }
   __syncthreads();
 }
 
@@ -246,7 +251,23 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   __shared__ LloydLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // this wavefront's unit of work, and its first row in flight before the prologue
+  // Wavefront 0 turns last iteration's sums into this iteration's tables while the
+  // others clear the histogram; its loads go out first so that nothing queues
+  // ahead of them.
+  if (wave == 0) {
+    const bool first = iteration == 0;
+    wave_make_tables(sm, first ? nullptr : state->acc[(iteration - 1) % 3],
+                     state->tables[first ? 0 : (iteration - 1) & 1]);
+    if (blockIdx.x == 0) {
+      if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.newtab[lane];
+      if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
+      for (int i = lane; i < kAccStride; i += 64) state->acc[(iteration + 1) % 3][i] = 0.0;
+    }
+  } else {
+    for (int i = tid - 64; i < 2 * 32 * kSlots; i += kLloydBlock - 64) (&sm.hist[0][0][0])[i] = 0.0;
+  }
+
+  // this wavefront's unit of work, and its first row in flight during the rest of the prologue
   const int unit = blockIdx.x * kLloydWaves + wave;
   const bool has_unit = unit < units;
   const int strip = has_unit ? unit % strips : 0;
@@ -266,20 +287,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   float Iv[8];
 #pragma unroll
   for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
-
-  // tables of this iteration: the initial grid, or the update of the previous ones
-  if (iteration == 0) {
-    if (tid < 32) sm.newtab[tid] = state->tables[0][tid];
-    __syncthreads();
-  } else {
-    update_tables(sm, state->acc[(iteration - 1) % 3], state->tables[(iteration - 1) & 1]);
-    if (blockIdx.x == 0) {
-      if (tid < 32) state->tables[iteration & 1][tid] = sm.newtab[tid];
-      if (tid == 32 && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
-    }
-  }
-  if (blockIdx.x == 0 && tid < kAccStride) state->acc[(iteration + 1) % 3][tid] = 0.0;
-  build_search_tables(sm);
+  __syncthreads();
+  build_bucket_table(sm);
   const float inv = sm.lutpar[0], off = sm.lutpar[1];
   const uint32_t rep4 = (uint32_t)(lane & (kReplicas - 1)) * 4u;
 
@@ -344,22 +353,21 @@ __global__ void init_state_kernel(Grid32 grid, FitState* state) {
 }
 
 // After the last iteration: update the tables from its sums and write the outputs.
-__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
-    FitState* __restrict__ state, int iterations, float* __restrict__ tables_f32,
-    uint16_t* __restrict__ tables_bf16, double* __restrict__ objective_trace) {
+__global__ __launch_bounds__(64) void final_tables_kernel(FitState* __restrict__ state, int iterations,
+                                                          float* __restrict__ tables_f32,
+                                                          uint16_t* __restrict__ tables_bf16,
+                                                          double* __restrict__ objective_trace) {
   __shared__ LloydLds sm;
-  const int tid = threadIdx.x;
-  if (iterations == 0) {
-    if (tid < 32) sm.newtab[tid] = state->tables[0][tid];
-  } else {
-    update_tables(sm, state->acc[(iterations - 1) % 3], state->tables[(iterations - 1) & 1]);
-    if (tid == 32 && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
-  }
-  __syncthreads();
-  if (tid < 32) {
-    const float t = sm.newtab[tid];
-    if (tables_f32) tables_f32[tid] = t;
-    tables_bf16[tid] = (uint16_t)bf16_rne(t);
+  const int lane = threadIdx.x;
+  const bool none = iterations == 0;
+  wave_make_tables(sm, none ? nullptr : state->acc[(iterations - 1) % 3],
+                   state->tables[none ? 0 : (iterations - 1) & 1]);
+  __builtin_amdgcn_wave_barrier();
+  if (lane == 32 && !none && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
+  if (lane < 32) {
+    const float t = sm.newtab[lane];
+    if (tables_f32) tables_f32[lane] = t;
+    tables_bf16[lane] = (uint16_t)bf16_rne(t);
   }
 }
 
@@ -442,7 +450,7 @@ hipError_t launch_fit(const void* W, const FitPlan& p, int fmt, const float* imp
     e = launch_fill_zero(objective_trace, sizeof(double) * iterations, stream);
     if (e != hipSuccess) return e;
   }
-  final_tables_kernel<<<1, kLloydBlock, 0, stream>>>(state, done, tables_f32, tables_bf16, objective_trace);
+  final_tables_kernel<<<1, 64, 0, stream>>>(state, done, tables_f32, tables_bf16, objective_trace);
   return hipGetLastError();
 }
 

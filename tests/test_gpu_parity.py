@@ -207,6 +207,26 @@ def test_distinct_initial_tables_and_padded_rows():
     assert (out[:, K:] == 0).all()
 
 
+@pytest.mark.parametrize("fmt,g", [(0, 16), (1, 128)])
+def test_clustered_and_duplicate_table_entries(fmt, g):
+    """Entries closer together than a search bucket, triples of equal entries and a
+    whole table collapsed to one value: the bucket search must fall back to the
+    plain count and still agree with the oracle."""
+    Wt = inputs.make_weight(96, 1024, "gauss_outlier", 91, DEV)
+    I = oracle.act_stats(inputs.bits(inputs.make_activations(64, 1024, ("gauss", 0.01, "u10_50"), 92, DEV)))
+    base = inputs.E2M1_GRID if fmt == 0 else inputs.INT4_GRID
+    t0 = base.copy()
+    t0[7:10] = [0.0, 0.004, 0.009]          # two midpoints inside one bucket, where the weights are dense
+    t1 = base.copy()
+    t1[4:7] = t1[5]                          # a triple: equal midpoints, an empty cell
+    t1[11:13] = t1[11] + np.float32([0.0, 1e-6])
+    check_layer(Wt, I, g, fmt, np.concatenate([t0, t1]).astype(np.float32), 3, "clustered")
+    flat = np.concatenate([base, np.full(16, 0.5, np.float32)]).astype(np.float32)
+    check_layer(Wt, I, g, fmt, flat, 2, "collapsed_table")
+    both_flat = np.concatenate([np.full(16, -0.25, np.float32), np.full(16, 0.5, np.float32)])
+    check_layer(Wt, I, g, fmt, both_flat, 2, "both_collapsed")
+
+
 def test_degenerate_inputs():
     # all-zero weights, zero importance, empty layer, zero iterations
     g = 16
