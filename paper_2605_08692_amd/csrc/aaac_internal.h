@@ -8,6 +8,7 @@ namespace aaac {
 
 constexpr int kStripCols = 512;      // columns covered by one wavefront: 64 lanes x 8 bf16
 constexpr int kAccStride = 72;       // doubles per accumulator: 32 sum I*x, 32 sum I, objective, pad
+constexpr int kAccCopies = 16;       // copies of an accumulator; block b adds to copy b % 16
 
 struct Grid32 {  // initial tables, passed to a kernel by value
   float t[32];
@@ -16,17 +17,19 @@ struct Grid32 {  // initial tables, passed to a kernel by value
 // Device-resident state of one layer's fit (lives at the start of its workspace).
 struct FitState {
   float tables[2][32];        // T0[16], T1[16] of iteration t at [t & 1], ascending
-  double acc[3][kAccStride];  // sums of iteration t at [t % 3]
+  double acc[3][kAccCopies][kAccStride];  // sums of iteration t at [t % 3], spread over copies
 };
 
-// How a layer is cut into wavefront work units for the Lloyd iteration.
+// How a layer is cut into blocks for the Lloyd iteration: a block owns a
+// rectangle of `strips_per_block` 512-column strips x `rows_per_block` rows.
 struct FitPlan {
   int64_t N, K, ldw;
   int group_size;
-  int strips;         // ceil(K / 512)
-  int rows_per_unit;  // rows handled by one wavefront
-  int64_t units;      // strips * ceil(N / rows_per_unit)
-  int blocks;         // ceil(units / 16)
+  int strips;            // ceil(K / 512)
+  int strips_per_block;  // 1, 2, 4, 8 or 16 (wavefront w works on strip w % strips_per_block)
+  int strip_groups;      // ceil(strips / strips_per_block)
+  int rows_per_block;
+  int blocks;            // strip_groups * ceil(N / rows_per_block)
   // workspace layout (byte offsets)
   size_t off_state, off_rinv, bytes;
 };

@@ -1,10 +1,13 @@
 // The fused Lloyd iteration (assignment step + accumulation of the table
 // update) for gfx950, and the launcher of a whole fit.
 //
-// Work mapping: a wavefront owns a strip of 512 columns (64 lanes x 8 bf16) and
-// a range of rows; a lane keeps the importances of its 8 columns in registers.
-// A group of g weights is held by g/8 adjacent lanes.  One block of 16
-// wavefronts per compute unit.
+// Work mapping: a block of 16 wavefronts (one per compute unit) owns a
+// rectangle of 1..16 strips of 512 columns x a range of rows.  A wavefront is
+// bound to one strip (64 lanes x 8 bf16; a lane keeps the importances of its 8
+// columns in registers) and takes rows of that strip one at a time from a
+// counter in LDS, so all wavefronts of a block finish together whatever order
+// the hardware favours them in.  A group of g weights is held by g/8 adjacent
+// lanes.
 //
 // Nearest-entry search.  The index of a normalised weight x in an ascending
 // table is the number of midpoints strictly below x.  Instead of 15 compares
@@ -66,6 +69,8 @@ struct alignas(16) LloydLds {
   float newtab[32];
   double sums[72];
   double red[kLloydWaves];
+  double copies[kAccCopies][kAccStride];  // the accumulator copies, staged by 16 wavefronts
+  int next_row[kLloydWaves];              // per strip of the block: next row to hand out
   uint32_t entry[2][kBuckets];            // unreplicated bucket entries while building
   uint32_t lut[2][kBuckets * kReplicas];  // per table: 16 * candidate row, replicated
 };
@@ -157,22 +162,27 @@ __device__ __forceinline__ void assign_slow(const float (&Iv)[8], const LloydLds
 }
 
 // Tables of an iteration, computed by ONE wavefront (all 64 lanes call it, no
-// block barrier inside): from the accumulated sums of the previous iteration
-// (acc[0..31] = sum I*x, acc[32..63] = sum I, acc[64] = objective) divide, keep
-// entries whose cell was empty, sort each table (stable); with acc == nullptr the
-// old tables are taken as they are.  Leaves the tables in sm.newtab, the
+// block barrier inside): from the accumulated sums of the previous iteration,
+// staged in sm.copies (per copy: [0..31] = sum I*x, [32..63] = sum I, [64] =
+// objective), divide, keep entries whose cell was empty, sort each table
+// (stable); without sums the old tables are taken as they are.  Leaves the tables in sm.newtab, the
 // objective in sm.sums[64], and fills the search rows, the bucket map parameters
 // and the bucket of every midpoint.  Lanes of one wavefront run in lockstep and
 // LDS accesses of a wavefront complete in order, so its stores are visible to
 // its own later loads; wave_barrier() only keeps the compiler from reordering.
-__device__ void wave_make_tables(LloydLds& sm, const double* __restrict__ acc,
-                                 const float* __restrict__ old_tables) {
+__device__ void wave_make_tables(LloydLds& sm, bool have_sums, const float* __restrict__ old_tables) {
   const int lane = threadIdx.x & 63;
   if (lane < 32) {
     float t = old_tables[lane];
-    if (acc != nullptr) {
-      const double num = acc[lane], den = acc[32 + lane];
-      if (lane == 0) sm.sums[64] = acc[64];
+    if (have_sums) {  // the copies are added in a fixed order
+      double num = 0.0, den = 0.0, obj = 0.0;
+#pragma unroll
+      for (int c = 0; c < kAccCopies; ++c) {
+        num += sm.copies[c][lane];
+        den += sm.copies[c][32 + lane];
+        if (lane == 0) obj += sm.copies[c][64];
+      }
+      if (lane == 0) sm.sums[64] = obj;
       if (den > 0.0) t = (float)(num / den);
     }
     sm.cand[lane] = t;
@@ -247,46 +257,61 @@ template <int LANES>
 __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
     const uint16_t* __restrict__ W, int N, int K, int64_t ldw, const float* __restrict__ rinv,
     const float* __restrict__ importance, FitState* __restrict__ state,
-    double* __restrict__ objective_trace, int iteration, int strips, int rows_per_unit, int units) {
+    double* __restrict__ objective_trace, int iteration, int strips, int strips_per_block, int strip_groups,
+    int rows_per_block) {
   __shared__ LloydLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // Wavefront 0 turns last iteration's sums into this iteration's tables while the
-  // others clear the histogram; its loads go out first so that nothing queues
-  // ahead of them.
-  if (wave == 0) {
-    const bool first = iteration == 0;
-    wave_make_tables(sm, first ? nullptr : state->acc[(iteration - 1) % 3],
-                     state->tables[first ? 0 : (iteration - 1) & 1]);
-    if (blockIdx.x == 0) {
-      if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.newtab[lane];
-      if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
-      for (int i = lane; i < kAccStride; i += 64) state->acc[(iteration + 1) % 3][i] = 0.0;
-    }
-  } else {
-    for (int i = tid - 64; i < 2 * 32 * kSlots; i += kLloydBlock - 64) (&sm.hist[0][0][0])[i] = 0.0;
+  // Each wavefront fetches one copy of last iteration's sums (these loads go out
+  // first, nothing queues ahead of them) and the histogram is cleared.
+  const bool first = iteration == 0;
+  double acc_val = 0.0, acc_obj = 0.0;
+  if (!first && wave < kAccCopies) {
+    const double* src = state->acc[(iteration - 1) % 3][wave];
+    acc_val = src[lane];
+    if (lane == 0) acc_obj = src[64];
   }
+  for (int i = tid; i < 2 * 32 * kSlots; i += kLloydBlock) (&sm.hist[0][0][0])[i] = 0.0;
 
-  // this wavefront's unit of work, and its first row in flight during the rest of the prologue
-  const int unit = blockIdx.x * kLloydWaves + wave;
-  const bool has_unit = unit < units;
-  const int strip = has_unit ? unit % strips : 0;
-  const int r0 = has_unit ? (unit / strips) * rows_per_unit : 0;
-  const int r1 = has_unit ? (r0 + rows_per_unit < N ? r0 + rows_per_unit : N) : 0;
+  // this block's rectangle and this wavefront's strip; the first rows are handed out
+  // statically (wavefront w takes row w / strips_per_block) and are in flight during the
+  // rest of the prologue
+  const int queue = wave % strips_per_block;
+  const int strip = (blockIdx.x % strip_groups) * strips_per_block + queue;
+  const int block_r0 = (blockIdx.x / strip_groups) * rows_per_block;
+  const int block_r1 = block_r0 + rows_per_block < N ? block_r0 + rows_per_block : N;
+  const int waves_per_queue = kLloydWaves / strips_per_block;
   const int col = strip * kStripCols + lane * 8;
-  const bool active = has_unit && col < K;
+  const bool has_strip = strip < strips;
+  const bool active = has_strip && col < K;
   const int G = K / (8 * LANES);
-  const uint16_t* wp = W + (int64_t)r0 * ldw + (active ? col : 0);
-  const float* rp = rinv + (int64_t)r0 * G + (active ? col / (8 * LANES) : 0);
+  const uint16_t* wbase = W + (active ? col : 0);
+  const float* rbase = rinv + (active ? col / (8 * LANES) : 0);
+  int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
+  if (tid < strips_per_block) sm.next_row[tid] = block_r0 + waves_per_queue;
   uint4 v_next = make_uint4(0, 0, 0, 0);
   float r_next = 0.0f;
-  if (active && r0 < r1) {
-    v_next = *reinterpret_cast<const uint4*>(wp);
-    r_next = *rp;
+  if (active && row < block_r1) {
+    v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)row * ldw);
+    r_next = rbase[(int64_t)row * G];
   }
   float Iv[8];
 #pragma unroll
   for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
+  if (!first && wave < kAccCopies) {
+    sm.copies[wave][lane] = acc_val;
+    if (lane == 0) sm.copies[wave][64] = acc_obj;
+  }
+  __syncthreads();
+  // wavefront 0 turns the sums into this iteration's tables
+  if (wave == 0) {
+    wave_make_tables(sm, !first, state->tables[first ? 0 : (iteration - 1) & 1]);
+    if (blockIdx.x == 0) {
+      if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.newtab[lane];
+      if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
+      for (int i = lane; i < kAccCopies * kAccStride; i += 64) (&state->acc[(iteration + 1) % 3][0][0])[i] = 0.0;
+    }
+  }
   __syncthreads();
   build_bucket_table(sm);
   const float inv = sm.lutpar[0], off = sm.lutpar[1];
@@ -298,15 +323,18 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   for (int p = 0; p < 8; ++p) Id[p] = (double)Iv[p];
   const uint32_t slot8 = (uint32_t)(lane & (kSlots - 1)) * 8u;
   char* hist = reinterpret_cast<char*>(&sm.hist[0][0][0]);
-  for (int row = r0; row < r1; ++row) {
+  while (row < block_r1) {
     const uint4 v = v_next;
     const float r = r_next;
-    wp += ldw;
-    rp += G;
-    if (active && row + 1 < r1) {  // next row's loads fly while this one is processed
-      v_next = *reinterpret_cast<const uint4*>(wp);
-      r_next = *rp;
+    // take the next row of this strip and start its loads before working on this one
+    int next = 0;
+    if (lane == 0) next = atomicAdd(&sm.next_row[queue], 1);
+    next = __builtin_amdgcn_readfirstlane(next);
+    if (active && next < block_r1) {
+      v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)next * ldw);
+      r_next = rbase[(int64_t)next * G];
     }
+    row = next;
     Lane8 a;
     assign_fast(unpack8(v), r, Iv, sm, inv, off, rep4, a);
     if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm, a);
@@ -331,7 +359,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   for (int o = 32; o > 0; o >>= 1) obj += __shfl_down(obj, o);
   if (lane == 0) sm.red[wave] = obj;
   __syncthreads();
-  double* acc = state->acc[iteration % 3];
+  double* acc = state->acc[iteration % 3][blockIdx.x % kAccCopies];
   if (tid < 64) {
     const double* h = &sm.hist[0][0][0] + tid * kSlots;
     double s = 0.0;
@@ -349,19 +377,24 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
 __global__ void init_state_kernel(Grid32 grid, FitState* state) {
   const int tid = threadIdx.x;
   if (tid < 32) state->tables[0][tid] = grid.t[tid];
-  for (int i = tid; i < 3 * kAccStride; i += blockDim.x) (&state->acc[0][0])[i] = 0.0;
+  for (int i = tid; i < 3 * kAccCopies * kAccStride; i += blockDim.x) (&state->acc[0][0][0])[i] = 0.0;
 }
 
 // After the last iteration: update the tables from its sums and write the outputs.
-__global__ __launch_bounds__(64) void final_tables_kernel(FitState* __restrict__ state, int iterations,
-                                                          float* __restrict__ tables_f32,
-                                                          uint16_t* __restrict__ tables_bf16,
-                                                          double* __restrict__ objective_trace) {
+__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
+    FitState* __restrict__ state, int iterations, float* __restrict__ tables_f32,
+    uint16_t* __restrict__ tables_bf16, double* __restrict__ objective_trace) {
   __shared__ LloydLds sm;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool none = iterations == 0;
-  wave_make_tables(sm, none ? nullptr : state->acc[(iterations - 1) % 3],
-                   state->tables[none ? 0 : (iterations - 1) & 1]);
+  if (!none && wave < kAccCopies) {
+    const double* src = state->acc[(iterations - 1) % 3][wave];
+    sm.copies[wave][lane] = src[lane];
+    if (lane == 0) sm.copies[wave][64] = src[64];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  wave_make_tables(sm, !none, state->tables[none ? 0 : (iterations - 1) & 1]);
   __builtin_amdgcn_wave_barrier();
   if (lane == 32 && !none && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
   if (lane < 32) {
@@ -394,8 +427,8 @@ hipError_t launch_iterations(const uint16_t* W, const FitPlan& p, const float* i
                              hipStream_t stream) {
   for (int it = 0; it < iterations; ++it) {
     lloyd_iter_kernel<LANES><<<p.blocks, kLloydBlock, 0, stream>>>(
-        W, (int)p.N, (int)p.K, p.ldw, rinv, importance, state, objective_trace, it, p.strips, p.rows_per_unit,
-        (int)p.units);
+        W, (int)p.N, (int)p.K, p.ldw, rinv, importance, state, objective_trace, it, p.strips, p.strips_per_block,
+        p.strip_groups, p.rows_per_block);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -409,14 +442,33 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
   p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size;
   p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
   const int64_t rows = N > 0 ? N : 1;
-  // One block of 16 wavefronts per compute unit and never more blocks than
-  // compute units, so that the whole grid is resident at once.
-  const int64_t max_units = (int64_t)kLloydWaves * compute_units();
-  int64_t chunks = max_units / p.strips;  // row chunks per strip
-  if (chunks < 1) chunks = 1;
-  p.rows_per_unit = (int)ceil_div(rows, chunks);
-  p.units = p.strips * ceil_div(rows, p.rows_per_unit);
-  p.blocks = (int)ceil_div(p.units, kLloydWaves);
+  // One block of 16 wavefronts per compute unit.  Among 1, 2, 4, 8, 16 strips per
+  // block take the choice that keeps the most wavefronts busy: as many blocks as
+  // possible without exceeding the compute units (all blocks resident at once, no
+  // second round), few wavefronts bound to strips past the last one, and at least
+  // one row per wavefront.
+  const int cus = compute_units();
+  double best = -1.0;
+  for (int spb = 1; spb <= kLloydWaves; spb *= 2) {
+    const int64_t groups = ceil_div(p.strips, spb);
+    int64_t chunks = cus / groups;  // row chunks per strip group
+    if (chunks < 1) chunks = 1;
+    const int64_t min_rows = kLloydWaves / spb;
+    const int64_t most = rows / min_rows > 0 ? rows / min_rows : 1;
+    if (chunks > most) chunks = most;
+    const int64_t rpb = ceil_div(rows, chunks);
+    const int64_t blocks = groups * ceil_div(rows, rpb);
+    const double used = (double)p.strips / (double)(groups * spb);  // wavefronts that have a strip
+    const double fill = blocks <= cus ? (double)blocks : (double)cus * cus / (double)blocks;
+    const double score = used * fill;
+    if (score > best * 1.0000001) {
+      best = score;
+      p.strips_per_block = spb;
+      p.strip_groups = (int)groups;
+      p.rows_per_block = (int)rpb;
+      p.blocks = (int)blocks;
+    }
+  }
   auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
   p.off_state = 0;
   p.off_rinv = align(sizeof(FitState));
@@ -450,7 +502,7 @@ hipError_t launch_fit(const void* W, const FitPlan& p, int fmt, const float* imp
     e = launch_fill_zero(objective_trace, sizeof(double) * iterations, stream);
     if (e != hipSuccess) return e;
   }
-  final_tables_kernel<<<1, 64, 0, stream>>>(state, done, tables_f32, tables_bf16, objective_trace);
+  final_tables_kernel<<<1, kLloydBlock, 0, stream>>>(state, done, tables_f32, tables_bf16, objective_trace);
   return hipGetLastError();
 }
 
