@@ -21,7 +21,8 @@
  *     importances are finite and the importances non-negative.
  *   - Matrix pointers may be NULL when N == 0 (nothing is read or written).
  *   - Shapes: K % group_size == 0, group_size in {16, 32, 64, 128}, leading
- *     dimensions >= K and multiples of 8, device matrices 16-byte aligned.
+ *     dimensions >= K and multiples of 8, device matrices and the importance
+ *     vector 16-byte aligned.
  */
 #ifndef AAAC_H_
 #define AAAC_H_

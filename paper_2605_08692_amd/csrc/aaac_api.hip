@@ -44,6 +44,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int check_layer(const aaac_layer_t& l, int group_size) {
   if ((l.W == nullptr && l.N > 0) || l.importance == nullptr || l.tables_bf16 == nullptr) return AAAC_ERR_NULL;
+  if (!aligned(l.importance, 16)) return AAAC_ERR_SHAPE;
   return check_matrix(l.W, l.N, l.K, l.ldw, group_size);
 }
 

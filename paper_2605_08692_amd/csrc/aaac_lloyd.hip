@@ -165,15 +165,16 @@ __device__ __forceinline__ void assign_slow(const float (&Iv)[8], const LloydLds
 // block barrier inside): from the accumulated sums of the previous iteration,
 // staged in sm.copies (per copy: [0..31] = sum I*x, [32..63] = sum I, [64] =
 // objective), divide, keep entries whose cell was empty, sort each table
-// (stable); without sums the old tables are taken as they are.  Leaves the tables in sm.newtab, the
+// (stable); without sums the old tables (lane b passes entry b) are taken as
+// they are.  Leaves the tables in sm.newtab, the
 // objective in sm.sums[64], and fills the search rows, the bucket map parameters
 // and the bucket of every midpoint.  Lanes of one wavefront run in lockstep and
 // LDS accesses of a wavefront complete in order, so its stores are visible to
 // its own later loads; wave_barrier() only keeps the compiler from reordering.
-__device__ void wave_make_tables(LloydLds& sm, bool have_sums, const float* __restrict__ old_tables) {
+__device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) {
   const int lane = threadIdx.x & 63;
   if (lane < 32) {
-    float t = old_tables[lane];
+    float t = old_entry;  // lane b holds entry b of the previous tables
     if (have_sums) {  // the copies are added in a fixed order
       double num = 0.0, den = 0.0, obj = 0.0;
 #pragma unroll
@@ -265,6 +266,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   // Each wavefront fetches one copy of last iteration's sums (these loads go out
   // first, nothing queues ahead of them) and the histogram is cleared.
   const bool first = iteration == 0;
+  float old_entry = 0.0f;
+  if (tid < 32) old_entry = state->tables[first ? 0 : (iteration - 1) & 1][tid];
   double acc_val = 0.0, acc_obj = 0.0;
   if (!first && wave < kAccCopies) {
     const double* src = state->acc[(iteration - 1) % 3][wave];
@@ -296,8 +299,15 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
     r_next = rbase[(int64_t)row * G];
   }
   float Iv[8];
-#pragma unroll
-  for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
+  {
+    float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+    if (active) {
+      lo = *reinterpret_cast<const float4*>(importance + col);
+      hi = *reinterpret_cast<const float4*>(importance + col + 4);
+    }
+    Iv[0] = lo.x; Iv[1] = lo.y; Iv[2] = lo.z; Iv[3] = lo.w;
+    Iv[4] = hi.x; Iv[5] = hi.y; Iv[6] = hi.z; Iv[7] = hi.w;
+  }
   if (!first && wave < kAccCopies) {
     sm.copies[wave][lane] = acc_val;
     if (lane == 0) sm.copies[wave][64] = acc_obj;
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   __syncthreads();
   // wavefront 0 turns the sums into this iteration's tables
   if (wave == 0) {
-    wave_make_tables(sm, !first, state->tables[first ? 0 : (iteration - 1) & 1]);
+    wave_make_tables(sm, !first, old_entry);
     if (blockIdx.x == 0) {
       if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.newtab[lane];
       if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
@@ -387,6 +397,8 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
   __shared__ LloydLds sm;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool none = iterations == 0;
+  float old_entry = 0.0f;
+  if (threadIdx.x < 32) old_entry = state->tables[none ? 0 : (iterations - 1) & 1][threadIdx.x];
   if (!none && wave < kAccCopies) {
     const double* src = state->acc[(iterations - 1) % 3][wave];
     sm.copies[wave][lane] = src[lane];
@@ -394,7 +406,7 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
   }
   __syncthreads();
   if (wave != 0) return;
-  wave_make_tables(sm, !none, state->tables[none ? 0 : (iterations - 1) & 1]);
+  wave_make_tables(sm, !none, old_entry);
   __builtin_amdgcn_wave_barrier();
   if (lane == 32 && !none && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
   if (lane < 32) {
