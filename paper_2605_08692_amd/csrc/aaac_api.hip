@@ -148,7 +148,7 @@ int aaac_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size
   int rc = check_matrix(W, N, K, ldw, group_size);
   if (rc) return rc;
   if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
-  if (!aligned(codes, 4) || !aligned(scales, 2)) return AAAC_ERR_SHAPE;
+  if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(importance, 16)) return AAAC_ERR_SHAPE;
   return from_hip(aaac::launch_encode(W, N, K, ldw, group_size, fmt, importance, tables_bf16, codes,
                                       scales, static_cast<hipStream_t>(hip_stream)));
 }

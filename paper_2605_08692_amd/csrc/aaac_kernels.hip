@@ -6,9 +6,10 @@
 // All fp32 arithmetic that decides a code or a selection bit is written as single
 // IEEE operations (the file is compiled with -ffp-contract=off).  This file holds
 // the importance, scale, encode and dequant kernels; the Lloyd iteration is in
-// aaac_lloyd.hip.
+// aaac_lloyd.hip, the nearest-entry search shared with it in aaac_search.h.
 #include "aaac_device.h"
 #include "aaac_internal.h"
+#include "aaac_search.h"
 
 namespace aaac {
 
@@ -16,56 +17,6 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
-
-// Index of the nearest entry: number of midpoints strictly below x.
-__device__ __forceinline__ int count_above(float x, const float (&m)[15]) {
-  int idx = 0;
-#pragma unroll
-  for (int i = 0; i < 15; ++i) idx += (x > m[i]) ? 1 : 0;
-  return idx;
-}
-
-__device__ __forceinline__ float tree8(const float (&u)[8]) {
-  return ((u[0] + u[1]) + (u[2] + u[3])) + ((u[4] + u[5]) + (u[6] + u[7]));
-}
-
-__device__ __forceinline__ void load_midpoints(const float* sT, float (&m0)[15], float (&m1)[15]) {
-#pragma unroll
-  for (int i = 0; i < 15; ++i) {
-    m0[i] = 0.5f * (sT[i] + sT[i + 1]);
-    m1[i] = 0.5f * (sT[16 + i] + sT[17 + i]);
-  }
-}
-
-// Assignment of one lane's 8 normalised weights under both tables.
-struct Assign8 {
-  float wn[8];
-  int i0[8], i1[8];
-  float e0, e1;  // group errors (identical in every lane of the group)
-};
-
-template <int LANES>
-__device__ __forceinline__ Assign8 assign8(const W8& x, float r, const float (&Iv)[8], const float* sT,
-                                           const float (&m0)[15], const float (&m1)[15]) {
-  Assign8 a;
-  float u0[8], u1[8];
-#pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    float wn = x.w[p] * r;
-    a.wn[p] = wn;
-    a.i0[p] = count_above(wn, m0);
-    a.i1[p] = count_above(wn, m1);
-    float d0 = wn - sT[a.i0[p]];
-    float d1 = wn - sT[16 + a.i1[p]];
-    float q0 = d0 * d0;
-    float q1 = d1 * d1;
-    u0[p] = Iv[p] * q0;
-    u1[p] = Iv[p] * q1;
-  }
-  a.e0 = group_sum<LANES>(tree8(u0));
-  a.e1 = group_sum<LANES>(tree8(u1));
-  return a;
-}
 
 // Scale of a group from its absmax; returns the unsigned stored code.
 template <int FMT>
@@ -182,41 +133,89 @@ __global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __re
 
 // ----------------------------------------------------------------- encode
 
+struct alignas(16) EncodeLds {
+  SearchTables st;
+  SearchLut sl;
+};
+
+// Same block / wavefront / row mapping and the same bucket-table search as the
+// Lloyd iteration; per row a lane recomputes its group's scale, takes both
+// errors, and writes 8 codes as one 32-bit store (the first lane of a group also
+// stores the scale with the selection bit).
 template <int LANES, int FMT>
-__global__ __launch_bounds__(kBlock) void encode_kernel(
-    const uint16_t* __restrict__ W, int64_t N, int64_t K, int64_t ldw,
-    const float* __restrict__ importance, const uint16_t* __restrict__ tables_bf16,
-    uint8_t* __restrict__ codes, void* __restrict__ scales) {
-  __shared__ float sT[32];
-  if (threadIdx.x < 32) sT[threadIdx.x] = __uint_as_float((uint32_t)tables_bf16[threadIdx.x] << 16);
-  __syncthreads();
-  float m0[15], m1[15];
-  load_midpoints(sT, m0, m1);
-  const int64_t cpr = K / 8;
-  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = c < N * cpr;
-  const int64_t row = active ? c / cpr : 0;
-  const int64_t col = active ? (c % cpr) * 8 : 0;
-  uint4 v = make_uint4(0, 0, 0, 0);
+__global__ __launch_bounds__(kSearchBlock) void encode_kernel(
+    const uint16_t* __restrict__ W, int N, int K, int64_t ldw, const float* __restrict__ importance,
+    const uint16_t* __restrict__ tables_bf16, uint8_t* __restrict__ codes, void* __restrict__ scales,
+    int strips, int strips_per_block, int strip_groups, int rows_per_block) {
+  __shared__ EncodeLds sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (wave == 0) {
+    if (lane < 32) sm.st.newtab[lane] = __uint_as_float((uint32_t)tables_bf16[lane] << 16);
+    wave_make_rows(sm.st);
+  }
+  const int queue = wave % strips_per_block;
+  const int strip = (blockIdx.x % strip_groups) * strips_per_block + queue;
+  const int block_r0 = (blockIdx.x / strip_groups) * rows_per_block;
+  const int block_r1 = block_r0 + rows_per_block < N ? block_r0 + rows_per_block : N;
+  const int waves_per_queue = kSearchWaves / strips_per_block;
+  const int col = strip * kStripCols + lane * 8;
+  const bool has_strip = strip < strips;
+  const bool active = has_strip && col < K;
+  const int G = K / (8 * LANES);
+  const uint16_t* wbase = W + (active ? col : 0);
+  int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
+  if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
+  uint4 v_next = make_uint4(0, 0, 0, 0);
+  if (active && row < block_r1) v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)row * ldw);
   float Iv[8];
+  {
+    float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+    if (active) {
+      lo = *reinterpret_cast<const float4*>(importance + col);
+      hi = *reinterpret_cast<const float4*>(importance + col + 4);
+    }
+    Iv[0] = lo.x; Iv[1] = lo.y; Iv[2] = lo.z; Iv[3] = lo.w;
+    Iv[4] = hi.x; Iv[5] = hi.y; Iv[6] = hi.z; Iv[7] = hi.w;
+  }
+  __syncthreads();
+  build_bucket_table(sm.st, sm.sl);
+  const float inv = sm.st.lutpar[0], off = sm.st.lutpar[1];
+  const uint32_t rep4 = (uint32_t)(lane & (kReplicas - 1)) * 4u;
+  while (row < block_r1) {
+    const uint4 v = v_next;
+    const int cur = row;
+    int next = 0;
+    if (lane == 0) next = atomicAdd(&sm.st.next_row[queue], 1);
+    next = __builtin_amdgcn_readfirstlane(next);
+    if (active && next < block_r1) v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)next * ldw);
+    row = next;
+    const W8 x = unpack8(v);
+    float s;
+    const uint32_t sc = scale_code<FMT>(group_max<LANES>(absmax8(x)), &s);
+    const float r = div_rn(1.0f, s);
+    Lane8 a;
+    assign_fast(x, r, Iv, sm.st, sm.sl, inv, off, rep4, a);
+    if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm.st, a);
+    const float e0 = group_sum<LANES>(a.p0);
+    const float e1 = group_sum<LANES>(a.p1);
+    const bool sigma = e1 < e0;
+    const uint64_t sigma_mask = __builtin_amdgcn_ballot_w64(sigma);
+    uint32_t packed = 0;
 #pragma unroll
-  for (int p = 0; p < 8; ++p) Iv[p] = active ? importance[col + p] : 0.0f;
-  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
-  W8 x = unpack8(v);
-  float s;
-  uint32_t sc = scale_code<FMT>(group_max<LANES>(absmax8(x)), &s);
-  float r = div_rn(1.0f, s);
-  Assign8 a = assign8<LANES>(x, r, Iv, sT, m0, m1);
-  const bool sigma = a.e1 < a.e0;
-  if (!active) return;
-  uint32_t packed = 0;
-#pragma unroll
-  for (int p = 0; p < 8; ++p) packed |= (uint32_t)(sigma ? a.i1[p] : a.i0[p]) << (4 * p);
-  *reinterpret_cast<uint32_t*>(codes + (row * K + col) / 2) = packed;
-  if ((threadIdx.x % LANES) == 0) {
-    const int64_t g = row * (K / (8 * LANES)) + col / (8 * LANES);
-    if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sigma ? 0x80u : 0u));
-    else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sigma ? 0x8000u : 0u));
+    for (int p = 0; p < 8; ++p) {
+      const uint32_t k = sigma ? a.k1[p] : a.k0[p];  // (16 * table + index) * kSlots * 8
+      const bool up = __builtin_amdgcn_inverse_ballot_w64((a.m0[p] & ~sigma_mask) | (a.m1[p] & sigma_mask));
+      const uint32_t idx = ((k / (kSlots * 8u)) & 15u) + (up ? 1u : 0u);
+      packed |= idx << (4 * p);
+    }
+    if (active) {
+      *reinterpret_cast<uint32_t*>(codes + ((int64_t)cur * K + col) / 2) = packed;
+      if ((lane % LANES) == 0) {
+        const int64_t g = (int64_t)cur * G + col / (8 * LANES);
+        if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sigma ? 0x80u : 0u));
+        else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sigma ? 0x8000u : 0u));
+      }
+    }
   }
 }
 
@@ -343,11 +342,15 @@ template <int LANES>
 static hipError_t launch_encode_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt,
                                       const float* importance, const uint16_t* tables_bf16,
                                       uint8_t* codes, void* scales, hipStream_t stream) {
-  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  const FitPlan p = make_fit_plan(N, K, ldw, 8 * LANES);
   if (fmt == 0)
-    encode_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, importance, tables_bf16, codes, scales);
+    encode_kernel<LANES, 0><<<p.blocks, kSearchBlock, 0, stream>>>(W, (int)N, (int)K, ldw, importance, tables_bf16,
+                                                                  codes, scales, p.strips, p.strips_per_block,
+                                                                  p.strip_groups, p.rows_per_block);
   else
-    encode_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, importance, tables_bf16, codes, scales);
+    encode_kernel<LANES, 1><<<p.blocks, kSearchBlock, 0, stream>>>(W, (int)N, (int)K, ldw, importance, tables_bf16,
+                                                                  codes, scales, p.strips, p.strips_per_block,
+                                                                  p.strip_groups, p.rows_per_block);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }

@@ -9,22 +9,7 @@
 // the hardware favours them in.  A group of g weights is held by g/8 adjacent
 // lanes.
 //
-// Nearest-entry search.  The index of a normalised weight x in an ascending
-// table is the number of midpoints strictly below x.  Instead of 15 compares
-// per table, the block builds (once per launch, in LDS) a bucket table over the
-// range of the midpoints: bucket(x) is a monotone function of x computed with
-// one fused multiply-add and a clamp, and for every bucket and table it stores
-// i = number of midpoints whose bucket is lower.  If at most one midpoint falls
-// into the bucket itself, that midpoint is m[i], and index = i + (x > m[i]) with
-// reconstruction T[i] or T[i+1]: one 16-byte LDS read {m[i], T[i], T[i+1]} and
-// one compare.  A bucket holding two or more midpoints of a table points at a
-// poisoned row (NaN entries); the NaN reaches the lane's error sum, the wavefront
-// notices and redoes that row with the plain 15-compare count.  Results are
-// identical either way.
-//
-// The bucket table is replicated 32 times (one copy per LDS bank column) so
-// that data-dependent look-ups do not conflict; the 17 rows of {m, T, T} need no
-// replication because distinct rows already sit in distinct banks.
+// Nearest entry: the bucket-table search of aaac_search.h.
 //
 // Table update.  sum I*x and sum I of the 32 bins go through fp64 LDS atomics
 // into a block-wide histogram with 32 slots per bin (slot = lane mod 32); each
@@ -38,127 +23,30 @@
 // is not fixed: sums can differ between runs in the last bits of an fp64.
 #include "aaac_device.h"
 #include "aaac_internal.h"
+#include "aaac_search.h"
 
 namespace aaac {
 
 namespace {
 
-constexpr int kLloydBlock = 1024;
-constexpr int kLloydWaves = kLloydBlock / kWave;
-constexpr int kBuckets = 256;
-constexpr int kReplicas = 32;
-constexpr int kSlots = 32;
-constexpr int kPoison = 16;  // search row that holds NaN entries
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-struct alignas(16) SearchRow {  // 16 bytes: one LDS read serves a compare, a select and the bin address
-  float thr;        // midpoint m[i] (+inf for i >= 15)
-  float lo, hi;     // T[i], T[i+1]
-  uint32_t bin;     // byte offset of bin (table, i) in the histogram
-};
+constexpr int kLloydBlock = kSearchBlock;
+constexpr int kLloydWaves = kSearchWaves;
 
 // The small arrays come first so that their LDS offsets fit the 16-bit offset
 // field of the DS instructions; the bucket tables go last.
 struct alignas(16) LloydLds {
-  SearchRow row[2][20];                   // rows 0..15, poison row 16
+  SearchTables st;
   double hist[2][32][kSlots];             // [0] = sum I*x, [1] = sum I
-  float lutpar[4];                        // inv, off of bucket_row()
-  int mid_bucket[2][16];                  // bucket of each midpoint
   float cand[32];
-  float newtab[32];
   double sums[72];
   double red[kLloydWaves];
   double copies[kAccCopies][kAccStride];  // the accumulator copies, staged by 16 wavefronts
-  int next_row[kLloydWaves];              // per strip of the block: next row to hand out
-  uint32_t entry[2][kBuckets];            // unreplicated bucket entries while building
-  uint32_t lut[2][kBuckets * kReplicas];  // per table: 16 * candidate row, replicated
+  SearchLut sl;
 };
-
-// Monotone map from a normalised weight to the byte offset of its bucket's
-// replica block (bucket * 128): integer part of fma(x, inv, off), read from the
-// mantissa of a float in [2^23, 2^24), clamped.
-__device__ __forceinline__ uint32_t bucket_row(float x, float inv, float off) {
-  float t = __builtin_fmaf(x, inv, off);
-  t = __builtin_amdgcn_fmed3f(t, 8388608.0f, 8388608.0f + 32767.0f);
-  return __float_as_uint(t) & 0x7F80u;
-}
 
 // fp64 add to global memory, performed by the memory system, visible device-wide.
 __device__ __forceinline__ void device_add(double* p, double v) {
   __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ float tree8(const float (&u)[8]) {
-  return ((u[0] + u[1]) + (u[2] + u[3])) + ((u[4] + u[5]) + (u[6] + u[7]));
-}
-
-// Per-lane result of the assignment of 8 weights.
-struct Lane8 {
-  float wn[8];
-  uint32_t k0[8], k1[8];  // histogram byte offset of the candidate row's bin under T0 / T1
-  uint64_t m0[8], m1[8];  // lane masks: weight lies above that row's midpoint, index is one higher
-  float p0, p1;           // the lane's partial error sums
-};
-
-__device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&Iv)[8], const LloydLds& sm,
-                                            float inv, float off, uint32_t rep4, Lane8& a) {
-  float u0[8], u1[8];
-  const char* lut = reinterpret_cast<const char*>(sm.lut);
-  const char* row0 = reinterpret_cast<const char*>(sm.row[0]);
-  const char* row1 = reinterpret_cast<const char*>(sm.row[1]);
-#pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    const float wn = x.w[p] * r;
-    a.wn[p] = wn;
-    const char* e = lut + (bucket_row(wn, inv, off) | rep4);
-    const uint32_t a0 = *reinterpret_cast<const uint32_t*>(e);
-    const uint32_t a1 = *reinterpret_cast<const uint32_t*>(e + sizeof(sm.lut[0]));
-    // each row is one 16-byte DS read; all four fields are used, so it is not narrowed
-    // (12-byte or split reads of these rows are several times slower)
-    const f32x4 s0 = *reinterpret_cast<const f32x4*>(row0 + a0);
-    const f32x4 s1 = *reinterpret_cast<const f32x4*>(row1 + a1);
-    const bool c0 = wn > s0.x;
-    const bool c1 = wn > s1.x;
-    const float d0 = wn - (c0 ? s0.z : s0.y);
-    const float d1 = wn - (c1 ? s1.z : s1.y);
-    a.k0[p] = __float_as_uint(s0.w);
-    a.k1[p] = __float_as_uint(s1.w);
-    a.m0[p] = __builtin_amdgcn_ballot_w64(c0);
-    a.m1[p] = __builtin_amdgcn_ballot_w64(c1);
-    const float q0 = d0 * d0;
-    const float q1 = d1 * d1;
-    u0[p] = Iv[p] * q0;
-    u1[p] = Iv[p] * q1;
-  }
-  a.p0 = tree8(u0);
-  a.p1 = tree8(u1);
-}
-
-// Same result by counting all 15 midpoints (rows that met a poisoned bucket).
-__device__ __forceinline__ void assign_slow(const float (&Iv)[8], const LloydLds& sm, Lane8& a) {
-  float u0[8], u1[8];
-#pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    const float wn = a.wn[p];
-    int i0 = 0, i1 = 0;
-    for (int j = 0; j < 15; ++j) {
-      i0 += wn > sm.row[0][j].thr ? 1 : 0;
-      i1 += wn > sm.row[1][j].thr ? 1 : 0;
-    }
-    a.k0[p] = sm.row[0][i0].bin;
-    a.k1[p] = sm.row[1][i1].bin;
-    a.m0[p] = 0;
-    a.m1[p] = 0;
-    const float d0 = wn - sm.row[0][i0].lo;
-    const float d1 = wn - sm.row[1][i1].lo;
-    const float q0 = d0 * d0;
-    const float q1 = d1 * d1;
-    u0[p] = Iv[p] * q0;
-    u1[p] = Iv[p] * q1;
-  }
-  a.p0 = tree8(u0);
-  a.p1 = tree8(u1);
 }
 
 // Tables of an iteration, computed by ONE wavefront (all 64 lanes call it, no
@@ -166,7 +54,7 @@ __device__ __forceinline__ void assign_slow(const float (&Iv)[8], const LloydLds
 // staged in sm.copies (per copy: [0..31] = sum I*x, [32..63] = sum I, [64] =
 // objective), divide, keep entries whose cell was empty, sort each table
 // (stable); without sums the old tables (lane b passes entry b) are taken as
-// they are.  Leaves the tables in sm.newtab, the
+// they are.  Leaves the tables in sm.st.newtab, the
 // objective in sm.sums[64], and fills the search rows, the bucket map parameters
 // and the bucket of every midpoint.  Lanes of one wavefront run in lockstep and
 // LDS accesses of a wavefront complete in order, so its stores are visible to
@@ -198,60 +86,9 @@ __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) 
       const float u = sm.cand[base + j];
       rank += (u < v || (u == v && j < i)) ? 1 : 0;
     }
-    sm.newtab[base + rank] = v;
+    sm.st.newtab[base + rank] = v;
   }
-  __builtin_amdgcn_wave_barrier();
-  if (lane < 40) {
-    const int r = lane / 20, i = lane % 20;
-    const float* T = sm.newtab + 16 * r;
-    SearchRow s;
-    s.thr = i < 15 ? 0.5f * (T[i] + T[i + 1]) : __builtin_inff();
-    s.lo = i < 16 ? T[i] : __builtin_nanf("");
-    s.hi = i < 15 ? T[i + 1] : __builtin_nanf("");
-    s.bin = (uint32_t)(16 * r + (i < 16 ? i : 0)) * (kSlots * 8u);
-    sm.row[r][i] = s;
-  }
-  __builtin_amdgcn_wave_barrier();
-  if (lane < 32) {
-    const float lo = fminf(sm.row[0][0].thr, sm.row[1][0].thr);
-    const float hi = fmaxf(sm.row[0][14].thr, sm.row[1][14].thr);
-    const float range = fmaxf(hi - lo, 1e-20f);
-    const float inv = (128.0f * (kBuckets - 2)) / range;  // buckets 1..254 span [lo, hi]
-    const float off = (128.0f - lo * inv) + 8388608.0f;
-    if (lane == 0) {
-      sm.lutpar[0] = inv;
-      sm.lutpar[1] = off;
-    }
-    const int r = lane >> 4, j = lane & 15;
-    sm.mid_bucket[r][j] = j < 15 ? (int)(bucket_row(sm.row[r][j].thr, inv, off) >> 7) : kBuckets;
-  }
-}
-
-// Bucket table from the midpoint buckets, replicated; all threads of the block
-// call it after wave_make_tables() and a barrier.  Ends with a barrier.
-__device__ void build_bucket_table(LloydLds& sm) {
-  const int tid = threadIdx.x;
-  if (tid < kBuckets) {
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      int below = 0, inside = 0;
-#pragma unroll
-      for (int j = 0; j < 15; ++j) {
-        const int bj = sm.mid_bucket[r][j];
-        below += bj < tid ? 1 : 0;
-        inside += bj == tid ? 1 : 0;
-      }
-      const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
-      sm.entry[r][tid] = 16u * row;
-    }
-  }
-  __syncthreads();
-  // replicate: thread -> (replica = tid % 32, buckets tid/32 + 32*k)
-  for (int b = tid / kReplicas; b < kBuckets; b += kLloydBlock / kReplicas) {
-    sm.lut[0][b * kReplicas + (tid % kReplicas)] = sm.entry[0][b];
-    sm.lut[1][b * kReplicas + (tid % kReplicas)] = sm.entry[1][b];
-  }
-  __syncthreads();
+  wave_make_rows(sm.st);
 }
 
 template <int LANES>
@@ -291,7 +128,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   const uint16_t* wbase = W + (active ? col : 0);
   const float* rbase = rinv + (active ? col / (8 * LANES) : 0);
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
-  if (tid < strips_per_block) sm.next_row[tid] = block_r0 + waves_per_queue;
+  if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
   uint4 v_next = make_uint4(0, 0, 0, 0);
   float r_next = 0.0f;
   if (active && row < block_r1) {
@@ -317,14 +154,14 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   if (wave == 0) {
     wave_make_tables(sm, !first, old_entry);
     if (blockIdx.x == 0) {
-      if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.newtab[lane];
+      if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.st.newtab[lane];
       if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
       for (int i = lane; i < kAccCopies * kAccStride; i += 64) (&state->acc[(iteration + 1) % 3][0][0])[i] = 0.0;
     }
   }
   __syncthreads();
-  build_bucket_table(sm);
-  const float inv = sm.lutpar[0], off = sm.lutpar[1];
+  build_bucket_table(sm.st, sm.sl);
+  const float inv = sm.st.lutpar[0], off = sm.st.lutpar[1];
   const uint32_t rep4 = (uint32_t)(lane & (kReplicas - 1)) * 4u;
 
   double obj = 0.0;
@@ -338,7 +175,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
     const float r = r_next;
     // take the next row of this strip and start its loads before working on this one
     int next = 0;
-    if (lane == 0) next = atomicAdd(&sm.next_row[queue], 1);
+    if (lane == 0) next = atomicAdd(&sm.st.next_row[queue], 1);
     next = __builtin_amdgcn_readfirstlane(next);
     if (active && next < block_r1) {
       v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)next * ldw);
@@ -346,8 +183,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
     }
     row = next;
     Lane8 a;
-    assign_fast(unpack8(v), r, Iv, sm, inv, off, rep4, a);
-    if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm, a);
+    assign_fast(unpack8(v), r, Iv, sm.st, sm.sl, inv, off, rep4, a);
+    if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm.st, a);
     const float e0 = group_sum<LANES>(a.p0);
     const float e1 = group_sum<LANES>(a.p1);
     const bool sigma = e1 < e0;
@@ -410,7 +247,7 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
   __builtin_amdgcn_wave_barrier();
   if (lane == 32 && !none && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
   if (lane < 32) {
-    const float t = sm.newtab[lane];
+    const float t = sm.st.newtab[lane];
     if (tables_f32) tables_f32[lane] = t;
     tables_bf16[lane] = (uint16_t)bf16_rne(t);
   }

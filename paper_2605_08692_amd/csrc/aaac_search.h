@@ -1,0 +1,196 @@
+// Nearest-entry search shared by the Lloyd iteration and the encode kernel.
+//
+// The index of a normalised weight x in an ascending 16-entry table is the number
+// of midpoints strictly below x.  Instead of 15 compares per table, a block
+// builds (once per launch, in LDS) a bucket table over the range of the
+// midpoints: bucket(x) is a monotone function of x computed with one fused
+// multiply-add and a clamp, and for every bucket and table it stores i = number
+// of midpoints whose bucket is lower.  If at most one midpoint falls into the
+// bucket itself, that midpoint is m[i], and index = i + (x > m[i]) with
+// reconstruction T[i] or T[i+1]: one 16-byte LDS read {m[i], T[i], T[i+1], bin}
+// and one compare.  A bucket holding two or more midpoints of a table points at a
+// poisoned row (NaN entries); the NaN reaches the lane's error sum, the wavefront
+// notices and redoes that row with the plain 15-compare count.  Results are
+// identical either way.
+//
+// The bucket table is replicated 32 times (one copy per LDS bank column) so
+// that data-dependent look-ups do not conflict; the 17 rows of {m, T, T, bin}
+// need no replication because distinct rows already sit in distinct banks.
+#pragma once
+#include "aaac_device.h"
+
+namespace aaac {
+
+constexpr int kSearchBlock = 1024;  // threads per block of the kernels that use the search
+constexpr int kSearchWaves = kSearchBlock / kWave;
+constexpr int kBuckets = 256;
+constexpr int kReplicas = 32;
+constexpr int kSlots = 32;          // histogram slots per bin; a bin is kSlots * 8 bytes
+constexpr int kPoison = 16;         // search row that holds NaN entries
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct alignas(16) SearchRow {  // 16 bytes: one LDS read serves a compare, a select and the bin address
+  float thr;        // midpoint m[i] (+inf for i >= 15)
+  float lo, hi;     // T[i], T[i+1]
+  uint32_t bin;     // (16 * table + i) * kSlots * 8: byte offset of the bin in a histogram
+};
+
+// Small search state; keep it at the start of the block's LDS so that its
+// offsets fit the 16-bit offset field of the DS instructions.
+struct alignas(16) SearchTables {
+  SearchRow row[2][20];         // rows 0..15, poison row 16
+  float lutpar[4];              // inv, off of bucket_row()
+  int mid_bucket[2][16];        // bucket of each midpoint
+  float newtab[32];             // the tables T0[16], T1[16], ascending
+  int next_row[kSearchWaves];   // per strip of the block: next row to hand out
+  uint32_t entry[2][kBuckets];  // unreplicated bucket entries while building
+};
+
+struct alignas(16) SearchLut {
+  uint32_t lut[2][kBuckets * kReplicas];  // per table: 16 * candidate row, replicated
+};
+
+// Monotone map from a normalised weight to the byte offset of its bucket's
+// replica block (bucket * 128): integer part of fma(x, inv, off), read from the
+// mantissa of a float in [2^23, 2^24), clamped.
+__device__ __forceinline__ uint32_t bucket_row(float x, float inv, float off) {
+  float t = __builtin_fmaf(x, inv, off);
+  t = __builtin_amdgcn_fmed3f(t, 8388608.0f, 8388608.0f + 32767.0f);
+  return __float_as_uint(t) & 0x7F80u;
+}
+
+__device__ __forceinline__ float tree8(const float (&u)[8]) {
+  return ((u[0] + u[1]) + (u[2] + u[3])) + ((u[4] + u[5]) + (u[6] + u[7]));
+}
+
+// Per-lane result of the assignment of 8 weights.
+struct Lane8 {
+  float wn[8];
+  uint32_t k0[8], k1[8];  // bin field of the candidate row under T0 / T1
+  uint64_t m0[8], m1[8];  // lane masks: weight lies above that row's midpoint, index is one higher
+  float p0, p1;           // the lane's partial error sums
+};
+
+__device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&Iv)[8], const SearchTables& st,
+                                            const SearchLut& sl, float inv, float off, uint32_t rep4, Lane8& a) {
+  float u0[8], u1[8];
+  const char* lut = reinterpret_cast<const char*>(sl.lut);
+  const char* row0 = reinterpret_cast<const char*>(st.row[0]);
+  const char* row1 = reinterpret_cast<const char*>(st.row[1]);
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const float wn = x.w[p] * r;
+    a.wn[p] = wn;
+    const char* e = lut + (bucket_row(wn, inv, off) | rep4);
+    const uint32_t a0 = *reinterpret_cast<const uint32_t*>(e);
+    const uint32_t a1 = *reinterpret_cast<const uint32_t*>(e + sizeof(sl.lut[0]));
+    // each row is one 16-byte DS read; all four fields are used, so it is not narrowed
+    // (12-byte or split reads of these rows are several times slower)
+    const f32x4 s0 = *reinterpret_cast<const f32x4*>(row0 + a0);
+    const f32x4 s1 = *reinterpret_cast<const f32x4*>(row1 + a1);
+    const bool c0 = wn > s0.x;
+    const bool c1 = wn > s1.x;
+    const float d0 = wn - (c0 ? s0.z : s0.y);
+    const float d1 = wn - (c1 ? s1.z : s1.y);
+    a.k0[p] = __float_as_uint(s0.w);
+    a.k1[p] = __float_as_uint(s1.w);
+    a.m0[p] = __builtin_amdgcn_ballot_w64(c0);
+    a.m1[p] = __builtin_amdgcn_ballot_w64(c1);
+    const float q0 = d0 * d0;
+    const float q1 = d1 * d1;
+    u0[p] = Iv[p] * q0;
+    u1[p] = Iv[p] * q1;
+  }
+  a.p0 = tree8(u0);
+  a.p1 = tree8(u1);
+}
+
+// Same result by counting all 15 midpoints (rows that met a poisoned bucket).
+__device__ __forceinline__ void assign_slow(const float (&Iv)[8], const SearchTables& st, Lane8& a) {
+  float u0[8], u1[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const float wn = a.wn[p];
+    int i0 = 0, i1 = 0;
+    for (int j = 0; j < 15; ++j) {
+      i0 += wn > st.row[0][j].thr ? 1 : 0;
+      i1 += wn > st.row[1][j].thr ? 1 : 0;
+    }
+    a.k0[p] = st.row[0][i0].bin;
+    a.k1[p] = st.row[1][i1].bin;
+    a.m0[p] = 0;
+    a.m1[p] = 0;
+    const float d0 = wn - st.row[0][i0].lo;
+    const float d1 = wn - st.row[1][i1].lo;
+    const float q0 = d0 * d0;
+    const float q1 = d1 * d1;
+    u0[p] = Iv[p] * q0;
+    u1[p] = Iv[p] * q1;
+  }
+  a.p0 = tree8(u0);
+  a.p1 = tree8(u1);
+}
+
+// Search rows, bucket map parameters and the bucket of every midpoint from the
+// tables in st.newtab.  Called by ONE wavefront (all 64 lanes), no block barrier
+// inside: lanes of a wavefront run in lockstep and its LDS accesses complete in
+// order, so its stores are visible to its own later loads; wave_barrier() only
+// keeps the compiler from reordering.
+__device__ __forceinline__ void wave_make_rows(SearchTables& st) {
+  const int lane = threadIdx.x & 63;
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 40) {
+    const int r = lane / 20, i = lane % 20;
+    const float* T = st.newtab + 16 * r;
+    SearchRow s;
+    s.thr = i < 15 ? 0.5f * (T[i] + T[i + 1]) : __builtin_inff();
+    s.lo = i < 16 ? T[i] : __builtin_nanf("");
+    s.hi = i < 15 ? T[i + 1] : __builtin_nanf("");
+    s.bin = (uint32_t)(16 * r + (i < 16 ? i : 0)) * (kSlots * 8u);
+    st.row[r][i] = s;
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < 32) {
+    const float lo = fminf(st.row[0][0].thr, st.row[1][0].thr);
+    const float hi = fmaxf(st.row[0][14].thr, st.row[1][14].thr);
+    const float range = fmaxf(hi - lo, 1e-20f);
+    const float inv = (128.0f * (kBuckets - 2)) / range;  // buckets 1..254 span [lo, hi]
+    const float off = (128.0f - lo * inv) + 8388608.0f;
+    if (lane == 0) {
+      st.lutpar[0] = inv;
+      st.lutpar[1] = off;
+    }
+    const int r = lane >> 4, j = lane & 15;
+    st.mid_bucket[r][j] = j < 15 ? (int)(bucket_row(st.row[r][j].thr, inv, off) >> 7) : kBuckets;
+  }
+}
+
+// Bucket table from the midpoint buckets, replicated; all kSearchBlock threads
+// of the block call it after wave_make_rows() and a barrier.  Ends with a barrier.
+__device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLut& sl) {
+  const int tid = threadIdx.x;
+  if (tid < kBuckets) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      int below = 0, inside = 0;
+#pragma unroll
+      for (int j = 0; j < 15; ++j) {
+        const int bj = st.mid_bucket[r][j];
+        below += bj < tid ? 1 : 0;
+        inside += bj == tid ? 1 : 0;
+      }
+      const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
+      st.entry[r][tid] = 16u * row;
+    }
+  }
+  __syncthreads();
+  // replicate: thread -> (replica = tid % 32, buckets tid/32 + 32*k)
+  for (int b = tid / kReplicas; b < kBuckets; b += kSearchBlock / kReplicas) {
+    sl.lut[0][b * kReplicas + (tid % kReplicas)] = st.entry[0][b];
+    sl.lut[1][b * kReplicas + (tid % kReplicas)] = st.entry[1][b];
+  }
+  __syncthreads();
+}
+
+}  // namespace aaac
