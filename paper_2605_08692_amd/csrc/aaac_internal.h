@@ -36,7 +36,7 @@ struct FitPlan {
 FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size);
 
 struct StatsPlan {
-  int strips;
+  int strips;             // column groups of 4096
   int token_chunks;       // blocks along the token axis
   int64_t tokens_per_chunk;
   size_t bytes;

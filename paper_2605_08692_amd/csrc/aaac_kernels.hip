@@ -16,7 +16,6 @@ namespace aaac {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kWavesPerBlock = kBlock / kWave;
 
 // Scale of a group from its absmax; returns the unsigned stored code.
 template <int FMT>
@@ -35,49 +34,71 @@ __device__ __forceinline__ uint32_t scale_code(float absmax, float* s) {
 
 // ------------------------------------------------------------ importance
 
-// Partial column sums of squares over one chunk of tokens.  Block = 4 waves on
-// the same 512 columns, wave w takes tokens t0+w, t0+w+4, ...; eight 16-byte
-// loads are in flight per lane.  X is read once, so the loads are non-temporal.
-__global__ __launch_bounds__(kBlock) void act_stats_partial_kernel(
+// Partial column sums of squares over one chunk of tokens.  A wavefront reads
+// whole rows of up to 4096 columns (eight 16-byte loads per lane, 8 KB
+// contiguous), two rows in flight, so that HBM is read in long sequential runs;
+// the 8 wavefronts of a block take every 8th row of the block's token chunk.  X
+// is read once, so the loads are non-temporal.  The wavefronts' fp64 partials
+// are added in wavefront order through LDS.
+constexpr int kStatsBlock = 512;
+constexpr int kStatsWaves = kStatsBlock / kWave;
+constexpr int kStatsStrips = 8;                          // strips of 512 columns per wavefront
+constexpr int kStatsCols = kStatsStrips * kStripCols;    // 4096
+__global__ __launch_bounds__(kStatsBlock) void act_stats_partial_kernel(
     const uint16_t* __restrict__ X, int64_t tokens, int64_t K, int64_t ldx, int64_t tokens_per_chunk,
     double* __restrict__ partials, int64_t Kpad) {
-  __shared__ double sred[kWavesPerBlock][kStripCols];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ double buf[kStatsCols];  // [(strip * 8 + p) * 64 + lane]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t col = (int64_t)blockIdx.x * kStripCols + lane * 8;
+  const int64_t col0 = (int64_t)blockIdx.x * kStatsCols + lane * 8;
   const int64_t t0 = (int64_t)blockIdx.y * tokens_per_chunk;
   const int64_t t1 = t0 + tokens_per_chunk < tokens ? t0 + tokens_per_chunk : tokens;
-  double acc[8];
+  double acc[kStatsStrips][8];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) acc[p] = 0.0;
-  if (col < K) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const uint16_t* base = X + col;
-    constexpr int kInFlight = 8;
-    for (int64_t t = t0 + wave; t < t1; t += kWavesPerBlock * kInFlight) {
-      u32x4 v[kInFlight];
+  for (int s = 0; s < kStatsStrips; ++s)
 #pragma unroll
-      for (int u = 0; u < kInFlight; ++u) {
-        const int64_t tu = t + (int64_t)u * kWavesPerBlock;
-        v[u] = u32x4{0u, 0u, 0u, 0u};
-        if (tu < t1) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + tu * ldx));
-      }
+    for (int p = 0; p < 8; ++p) acc[s][p] = 0.0;
+  const uint16_t* base = X + col0;
+  for (int64_t t = t0 + wave; t < t1; t += 2 * kStatsWaves) {
+    u32x4 v[2][kStatsStrips];
 #pragma unroll
-      for (int u = 0; u < kInFlight; ++u) {
-        W8 x = unpack8(make_uint4(v[u].x, v[u].y, v[u].z, v[u].w));
+    for (int u = 0; u < 2; ++u) {
+      const int64_t tu = t + (int64_t)u * kStatsWaves;
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          double d = (double)x.w[p];
-          acc[p] = fma(d, d, acc[p]);
-        }
+      for (int s = 0; s < kStatsStrips; ++s) {
+        v[u][s] = u32x4{0u, 0u, 0u, 0u};
+        if (tu < t1 && col0 + s * kStripCols < K)
+          v[u][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + tu * ldx + s * kStripCols));
       }
     }
-  }
 #pragma unroll
-  for (int p = 0; p < 8; ++p) sred[wave][lane * 8 + p] = acc[p];
-  __syncthreads();
-  for (int c = threadIdx.x; c < kStripCols; c += kBlock) {
-    double s = (sred[0][c] + sred[1][c]) + (sred[2][c] + sred[3][c]);
-    partials[(int64_t)blockIdx.y * Kpad + (int64_t)blockIdx.x * kStripCols + c] = s;
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int s = 0; s < kStatsStrips; ++s) {
+        const W8 x = unpack8(make_uint4(v[u][s].x, v[u][s].y, v[u][s].z, v[u][s].w));
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const double d = (double)x.w[p];
+          acc[s][p] = fma(d, d, acc[s][p]);
+        }
+      }
+  }
+  for (int w = 0; w < kStatsWaves; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int s = 0; s < kStatsStrips; ++s)
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const int i = (s * 8 + p) * 64 + lane;
+          buf[i] = w == 0 ? acc[s][p] : buf[i] + acc[s][p];
+        }
+    }
+    __syncthreads();
+  }
+  double* out = partials + (int64_t)blockIdx.y * Kpad + (int64_t)blockIdx.x * kStatsCols;
+  for (int c = threadIdx.x; c < kStatsCols; c += kStatsBlock) {
+    const int s = c / kStripCols, l = (c % kStripCols) / 8, p = c % 8;
+    out[c] = buf[(s * 8 + p) * 64 + l];
   }
 }
 
@@ -276,15 +297,16 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t stream) {  // bytes % 4 
 
 StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
   StatsPlan p;
-  p.strips = (int)ceil_div(K, kStripCols);
-  int64_t want = ceil_div(2048, p.strips);           // about 8 blocks per CU in total
-  int64_t most = ceil_div(tokens > 0 ? tokens : 1, 64);  // at least 16 tokens per wavefront
-  int64_t chunks = want < most ? want : most;
+  p.strips = (int)ceil_div(K, kStatsCols);  // column groups of 4096
+  const int64_t tok = tokens > 0 ? tokens : 1;
+  int64_t chunks = ceil_div(256, p.strips);       // about one block of 8 wavefronts per compute unit
+  const int64_t most = ceil_div(tok, 4 * kStatsWaves);  // at least 4 rows per wavefront
+  if (chunks > most) chunks = most;
   if (chunks < 1) chunks = 1;
   if (chunks > 65535) chunks = 65535;
-  p.tokens_per_chunk = ceil_div(ceil_div(tokens > 0 ? tokens : 1, chunks), 4) * 4;
-  p.token_chunks = (int)ceil_div(tokens > 0 ? tokens : 1, p.tokens_per_chunk);
-  p.bytes = (size_t)p.token_chunks * p.strips * kStripCols * sizeof(double);
+  p.tokens_per_chunk = ceil_div(ceil_div(tok, chunks), kStatsWaves) * kStatsWaves;
+  p.token_chunks = (int)ceil_div(tok, p.tokens_per_chunk);
+  p.bytes = (size_t)p.token_chunks * p.strips * kStatsCols * sizeof(double);
   return p;
 }
 
@@ -298,12 +320,12 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
 
 hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
                             void* ws, const StatsPlan& plan, hipStream_t stream) {
-  const int64_t Kpad = (int64_t)plan.strips * kStripCols;
+  const int64_t Kpad = (int64_t)plan.strips * kStatsCols;
   double* partials = static_cast<double*>(ws);
   if (tokens == 0) {
     return fill_zero(importance, (size_t)K * sizeof(float), stream);
   }
-  act_stats_partial_kernel<<<dim3(plan.strips, plan.token_chunks), kBlock, 0, stream>>>(
+  act_stats_partial_kernel<<<dim3(plan.strips, plan.token_chunks), kStatsBlock, 0, stream>>>(
       static_cast<const uint16_t*>(X), tokens, K, ldx, plan.tokens_per_chunk, partials, Kpad);
   AAAC_LAUNCH_CHECK();
   act_stats_reduce_kernel<<<(unsigned)ceil_div(K, 16), kBlock, 0, stream>>>(partials, plan.token_chunks,
