@@ -129,13 +129,17 @@ int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaa
   for (int i = 0; i < 32; ++i) grid.t[i] = init_grid[i];
   char* base = static_cast<char*>(ws);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  for (int i = 0; i < n_layers; ++i) {
-    const aaac_layer_t& l = layers[i];
-    aaac::FitPlan plan = aaac::make_fit_plan(l.N, l.K, l.ldw, group_size);
-    hipError_t e = aaac::launch_fit(l.W, plan, fmt, l.importance, grid, iterations, l.tables_f32,
-                                    l.tables_bf16, l.objective_trace, base, stream);
-    if (e != hipSuccess) return AAAC_ERR_HIP;
-    base += align256(plan.bytes);
+  // the layers are fitted in groups whose iterations share one launch each
+  for (int first = 0; first < n_layers; first += aaac::kMaxFusedLayers) {
+    aaac::FitTask tasks[aaac::kMaxFusedLayers];
+    int n = 0;
+    for (int i = first; i < n_layers && n < aaac::kMaxFusedLayers; ++i, ++n) {
+      const aaac_layer_t& l = layers[i];
+      tasks[n] = {l.W, l.N, l.K, l.ldw, l.importance, l.tables_f32, l.tables_bf16, l.objective_trace, base};
+      base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size).bytes);
+    }
+    if (aaac::launch_fit_group(tasks, n, group_size, fmt, grid, iterations, stream) != hipSuccess)
+      return AAAC_ERR_HIP;
   }
   return AAAC_OK;
 }

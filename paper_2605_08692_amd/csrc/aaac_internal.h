@@ -33,7 +33,8 @@ struct FitPlan {
   // workspace layout (byte offsets)
   size_t off_state, off_rinv, bytes;
 };
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size);
+// cu_budget: compute units this layer may fill (0 = all of the device's).
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_budget = 0);
 
 struct StatsPlan {
   int strips;             // column groups of 4096
@@ -45,9 +46,20 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K);
 
 hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
                             void* ws, const StatsPlan& plan, hipStream_t stream);
-hipError_t launch_fit(const void* W, const FitPlan& plan, int fmt, const float* importance,
-                      const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
-                      double* objective_trace, void* ws, hipStream_t stream);
+// One layer of a fit as the launcher sees it (host side).
+struct FitTask {
+  const void* W;
+  int64_t N, K, ldw;
+  const float* importance;
+  float* tables_f32;
+  uint16_t* tables_bf16;
+  double* objective_trace;
+  void* ws;  // this layer's workspace (make_fit_plan(...).bytes)
+};
+constexpr int kMaxFusedLayers = 8;  // layers whose iterations share one launch
+// Fits n <= kMaxFusedLayers layers together: one launch per iteration covers all of them.
+hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
+                            int iterations, hipStream_t stream);
 hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
                              float* rinv, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);

@@ -7,7 +7,9 @@
 // columns in registers) and takes rows of that strip one at a time from a
 // counter in LDS, so all wavefronts of a block finish together whatever order
 // the hardware favours them in.  A group of g weights is held by g/8 adjacent
-// lanes.
+// lanes.  Up to eight layers are fitted by the same launches: the grid is split
+// among them in proportion to their sizes and a block first looks up the layer
+// it belongs to.
 //
 // Nearest entry: the bucket-table search of aaac_search.h.
 //
@@ -42,6 +44,27 @@ struct alignas(16) LloydLds {
   double red[kLloydWaves];
   double copies[kAccCopies][kAccStride];  // the accumulator copies, staged by 16 wavefronts
   SearchLut sl;
+};
+
+// One layer as a block sees it.  Passed to the kernels by value.
+struct LayerArgs {
+  const uint16_t* W;
+  const float* rinv;
+  const float* importance;
+  FitState* state;
+  double* objective_trace;
+  float* tables_f32;      // outputs of the final kernel
+  uint16_t* tables_bf16;
+  int64_t ldw;
+  int N, K;
+  int strips, strips_per_block, strip_groups, rows_per_block;
+  int block_begin;  // first block of this layer in the grid
+  int pad;
+};
+struct BatchArgs {
+  int n;
+  int pad;
+  LayerArgs layer[kMaxFusedLayers];
 };
 
 // fp64 add to global memory, performed by the memory system, visible device-wide.
@@ -92,13 +115,21 @@ __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) 
 }
 
 template <int LANES>
-__global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
-    const uint16_t* __restrict__ W, int N, int K, int64_t ldw, const float* __restrict__ rinv,
-    const float* __restrict__ importance, FitState* __restrict__ state,
-    double* __restrict__ objective_trace, int iteration, int strips, int strips_per_block, int strip_groups,
-    int rows_per_block) {
+__global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs batch, const int iteration) {
   __shared__ LloydLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int li = 0;
+  for (int i = 1; i < batch.n; ++i) li = (int)blockIdx.x >= batch.layer[i].block_begin ? i : li;
+  const LayerArgs& L = batch.layer[li];
+  const uint16_t* __restrict__ W = L.W;
+  const float* __restrict__ rinv = L.rinv;
+  const float* __restrict__ importance = L.importance;
+  FitState* __restrict__ state = L.state;
+  double* __restrict__ objective_trace = L.objective_trace;
+  const int64_t ldw = L.ldw;
+  const int N = L.N, K = L.K, strips = L.strips, strips_per_block = L.strips_per_block,
+            strip_groups = L.strip_groups, rows_per_block = L.rows_per_block;
+  const int bid = (int)blockIdx.x - L.block_begin;  // block index inside the layer
 
   // Each wavefront fetches one copy of last iteration's sums (these loads go out
   // first, nothing queues ahead of them) and the histogram is cleared.
@@ -117,8 +148,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   // statically (wavefront w takes row w / strips_per_block) and are in flight during the
   // rest of the prologue
   const int queue = wave % strips_per_block;
-  const int strip = (blockIdx.x % strip_groups) * strips_per_block + queue;
-  const int block_r0 = (blockIdx.x / strip_groups) * rows_per_block;
+  const int strip = (bid % strip_groups) * strips_per_block + queue;
+  const int block_r0 = (bid / strip_groups) * rows_per_block;
   const int block_r1 = block_r0 + rows_per_block < N ? block_r0 + rows_per_block : N;
   const int waves_per_queue = kLloydWaves / strips_per_block;
   const int col = strip * kStripCols + lane * 8;
@@ -153,7 +184,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   // wavefront 0 turns the sums into this iteration's tables
   if (wave == 0) {
     wave_make_tables(sm, !first, old_entry);
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
       if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.st.newtab[lane];
       if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
       for (int i = lane; i < kAccCopies * kAccStride; i += 64) (&state->acc[(iteration + 1) % 3][0][0])[i] = 0.0;
@@ -206,7 +237,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   for (int o = 32; o > 0; o >>= 1) obj += __shfl_down(obj, o);
   if (lane == 0) sm.red[wave] = obj;
   __syncthreads();
-  double* acc = state->acc[iteration % 3][blockIdx.x % kAccCopies];
+  double* acc = state->acc[iteration % 3][bid % kAccCopies];
   if (tid < 64) {
     const double* h = &sm.hist[0][0][0] + tid * kSlots;
     double s = 0.0;
@@ -221,17 +252,20 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(
   }
 }
 
-__global__ void init_state_kernel(Grid32 grid, FitState* state) {
+// One block per layer: initial tables, cleared accumulators.
+__global__ void init_state_kernel(const BatchArgs batch, const Grid32 grid) {
+  FitState* state = batch.layer[blockIdx.x].state;
   const int tid = threadIdx.x;
   if (tid < 32) state->tables[0][tid] = grid.t[tid];
   for (int i = tid; i < 3 * kAccCopies * kAccStride; i += blockDim.x) (&state->acc[0][0][0])[i] = 0.0;
 }
 
-// After the last iteration: update the tables from its sums and write the outputs.
-__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
-    FitState* __restrict__ state, int iterations, float* __restrict__ tables_f32,
-    uint16_t* __restrict__ tables_bf16, double* __restrict__ objective_trace) {
+// After the last iteration, one block per layer: update the tables from its sums
+// and write the outputs.
+__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchArgs batch, const int iterations) {
   __shared__ LloydLds sm;
+  const LayerArgs& L = batch.layer[blockIdx.x];
+  FitState* __restrict__ state = L.state;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool none = iterations == 0;
   float old_entry = 0.0f;
@@ -245,11 +279,11 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(
   if (wave != 0) return;
   wave_make_tables(sm, !none, old_entry);
   __builtin_amdgcn_wave_barrier();
-  if (lane == 32 && !none && objective_trace) objective_trace[iterations - 1] = sm.sums[64];
+  if (lane == 32 && !none && L.objective_trace) L.objective_trace[iterations - 1] = sm.sums[64];
   if (lane < 32) {
     const float t = sm.st.newtab[lane];
-    if (tables_f32) tables_f32[lane] = t;
-    tables_bf16[lane] = (uint16_t)bf16_rne(t);
+    if (L.tables_f32) L.tables_f32[lane] = t;
+    L.tables_bf16[lane] = (uint16_t)bf16_rne(t);
   }
 }
 
@@ -271,13 +305,9 @@ int compute_units() {
 }
 
 template <int LANES>
-hipError_t launch_iterations(const uint16_t* W, const FitPlan& p, const float* importance, int iterations,
-                             FitState* state, const float* rinv, double* objective_trace,
-                             hipStream_t stream) {
+hipError_t launch_iterations(const BatchArgs& batch, int blocks, int iterations, hipStream_t stream) {
   for (int it = 0; it < iterations; ++it) {
-    lloyd_iter_kernel<LANES><<<p.blocks, kLloydBlock, 0, stream>>>(
-        W, (int)p.N, (int)p.K, p.ldw, rinv, importance, state, objective_trace, it, p.strips, p.strips_per_block,
-        p.strip_groups, p.rows_per_block);
+    lloyd_iter_kernel<LANES><<<blocks, kLloydBlock, 0, stream>>>(batch, it);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -286,7 +316,7 @@ hipError_t launch_iterations(const uint16_t* W, const FitPlan& p, const float* i
 
 }  // namespace
 
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_budget) {
   FitPlan p;
   p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size;
   p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
@@ -296,7 +326,7 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
   // possible without exceeding the compute units (all blocks resident at once, no
   // second round), few wavefronts bound to strips past the last one, and at least
   // one row per wavefront.
-  const int cus = compute_units();
+  const int cus = cu_budget > 0 ? cu_budget : compute_units();
   double best = -1.0;
   for (int spb = 1; spb <= kLloydWaves; spb *= 2) {
     const int64_t groups = ceil_div(p.strips, spb);
@@ -325,34 +355,86 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size) {
   return p;
 }
 
-hipError_t launch_fit(const void* W, const FitPlan& p, int fmt, const float* importance,
-                      const Grid32& grid, int iterations, float* tables_f32, uint16_t* tables_bf16,
-                      double* objective_trace, void* ws, hipStream_t stream) {
-  char* base = static_cast<char*>(ws);
-  FitState* state = reinterpret_cast<FitState*>(base + p.off_state);
-  float* rinv = reinterpret_cast<float*>(base + p.off_rinv);
-  init_state_kernel<<<1, 64, 0, stream>>>(grid, state);
+hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
+                            int iterations, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  // every layer gets its state initialised and its outputs written; only layers
+  // that hold weights take part in the iterations
+  BatchArgs all = {}, work = {};
+  double total = 0.0;
+  for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
+  const int cus = compute_units();
+  int blocks = 0;
+  for (int i = 0; i < n; ++i) {
+    const FitTask& t = tasks[i];
+    const double share = total > 0.0 ? (double)t.N * (double)t.K / total : 0.0;
+    int budget = (int)(share * cus);
+    if (budget < 1) budget = 1;
+    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, n == 1 ? 0 : budget);
+    char* base = static_cast<char*>(t.ws);
+    LayerArgs a = {};
+    a.W = static_cast<const uint16_t*>(t.W);
+    a.rinv = reinterpret_cast<const float*>(base + p.off_rinv);
+    a.importance = t.importance;
+    a.state = reinterpret_cast<FitState*>(base + p.off_state);
+    a.objective_trace = t.objective_trace;
+    a.tables_f32 = t.tables_f32;
+    a.tables_bf16 = t.tables_bf16;
+    a.ldw = t.ldw;
+    a.N = (int)t.N;
+    a.K = (int)t.K;
+    a.strips = p.strips;
+    a.strips_per_block = p.strips_per_block;
+    a.strip_groups = p.strip_groups;
+    a.rows_per_block = p.rows_per_block;
+    all.layer[all.n++] = a;
+    if (t.N > 0 && t.K > 0) {
+      a.block_begin = blocks;
+      blocks += p.blocks;
+      work.layer[work.n++] = a;
+    }
+  }
+  init_state_kernel<<<all.n, 256, 0, stream>>>(all, grid);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   int done = 0;
-  if (p.N > 0 && p.K > 0 && iterations > 0) {
-    const uint16_t* Wp = static_cast<const uint16_t*>(W);
-    e = launch_group_rinv(W, p.N, p.K, p.ldw, p.group_size, fmt, rinv, stream);
-    if (e != hipSuccess) return e;
-    switch (p.group_size / 8) {
-      case 2: e = launch_iterations<2>(Wp, p, importance, iterations, state, rinv, objective_trace, stream); break;
-      case 4: e = launch_iterations<4>(Wp, p, importance, iterations, state, rinv, objective_trace, stream); break;
-      case 8: e = launch_iterations<8>(Wp, p, importance, iterations, state, rinv, objective_trace, stream); break;
-      default: e = launch_iterations<16>(Wp, p, importance, iterations, state, rinv, objective_trace, stream); break;
+  if (work.n > 0 && iterations > 0) {
+    for (int i = 0; i < work.n; ++i) {
+      const LayerArgs& a = work.layer[i];
+      e = launch_group_rinv(a.W, a.N, a.K, a.ldw, group_size, fmt, const_cast<float*>(a.rinv), stream);
+      if (e != hipSuccess) return e;
+    }
+    switch (group_size / 8) {
+      case 2: e = launch_iterations<2>(work, blocks, iterations, stream); break;
+      case 4: e = launch_iterations<4>(work, blocks, iterations, stream); break;
+      case 8: e = launch_iterations<8>(work, blocks, iterations, stream); break;
+      default: e = launch_iterations<16>(work, blocks, iterations, stream); break;
     }
     if (e != hipSuccess) return e;
     done = iterations;
-  } else if (objective_trace && iterations > 0) {
-    e = launch_fill_zero(objective_trace, sizeof(double) * iterations, stream);
+  }
+  // layers without weights: the objective is zero and the tables stay the initial grid
+  for (int i = 0; i < n; ++i) {
+    const FitTask& t = tasks[i];
+    if (!(t.N > 0 && t.K > 0) && t.objective_trace && iterations > 0) {
+      e = launch_fill_zero(t.objective_trace, sizeof(double) * iterations, stream);
+      if (e != hipSuccess) return e;
+    }
+  }
+  if (work.n > 0) {
+    final_tables_kernel<<<work.n, kLloydBlock, 0, stream>>>(work, done);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  final_tables_kernel<<<1, kLloydBlock, 0, stream>>>(state, done, tables_f32, tables_bf16, objective_trace);
-  return hipGetLastError();
+  BatchArgs empty = {};
+  for (int i = 0; i < all.n; ++i)
+    if (!(all.layer[i].N > 0 && all.layer[i].K > 0)) empty.layer[empty.n++] = all.layer[i];
+  if (empty.n > 0) {
+    final_tables_kernel<<<empty.n, kLloydBlock, 0, stream>>>(empty, 0);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace aaac

@@ -276,6 +276,27 @@ def test_batch_matches_single_calls():
         assert np.allclose(host(ob)[:4], ref["objective"], rtol=1e-9)
 
 
+def test_batch_of_more_layers_than_one_launch_group_and_an_empty_layer():
+    shapes = [(64, 512), (8, 1024), (0, 512), (200, 512), (33, 1536), (16, 512), (128, 1024), (5, 512), (77, 2048),
+              (40, 512), (256, 512)]
+    g, fmt, iters = 16, 0, 3
+    Ws = [inputs.make_weight(N, K, "gauss_outlier", 700 + i, DEV) if N else
+          torch.empty((0, K), dtype=torch.bfloat16, device=DEV) for i, (N, K) in enumerate(shapes)]
+    Is = [torch.rand(K, device=DEV) + 0.05 for _, K in shapes]
+    layers, outs = A.make_layers(Ws, Is, iters)
+    ws = torch.empty(A.aaac_fit_batch_workspace(layers, g, fmt), dtype=torch.uint8, device=DEV)
+    A.aaac_fit_batch(layers, g, fmt, inputs.format_grid(fmt), iters, ws)
+    torch.cuda.synchronize()
+    for (N, K), W, I, (tf, tb, ob) in zip(shapes, Ws, Is, outs):
+        if N == 0:
+            assert (host(tf) == inputs.format_grid(fmt)).all() and (host(ob)[:iters] == 0).all()
+            continue
+        ref = oracle.fit(inputs.bits(W), g, fmt, host(I), inputs.format_grid(fmt), iters)
+        assert (u16(tb) == ref["tables_bf16"]).all(), (N, K)
+        assert tables_close(host(tf), ref["tables_f32"])
+        assert np.allclose(host(ob)[:iters], ref["objective"], rtol=1e-9)
+
+
 # ------------------------------------------ benchmark settings, full size
 
 def test_config0_full():
