@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the AAAC hot path on one MI355X.
 
-A step is one pass of the whole path over one synthetic layer that is already
-resident in HBM: aaac_act_stats (importance from the calibration activations),
-aaac_fit (scales + all Lloyd iterations), aaac_encode, aaac_dequant.  The
-workload at --gpus 1 is the Llama-2-7B-shaped q_proj setting (4096x4096 bf16,
-65,536 calibration tokens, INT4 group 128, 20 iterations).
+A step is one pass of the whole path over synthetic layers that are already
+resident in HBM: aaac_act_stats (importance from the calibration activations,
+once per distinct input width), aaac_fit / aaac_fit_batch (scales + all Lloyd
+iterations), aaac_encode and aaac_dequant for every layer.  The default workload
+is the Llama-2-7B-shaped q_proj setting (4096x4096 bf16, 65,536 calibration
+tokens, INT4 group 128, 20 iterations); --config selects another of the five
+benchmark settings.
 
 Prints one JSON line.  `value` is weight-iterations per second over the whole
-step (N*K*iterations / step time).  `roofline` describes the Lloyd-iteration
-kernel: its average duration is measured with HIP events on the launch stream
-around every aaac_fit call inside the timed region (fit time / iterations, so
-launch gaps and the small scale / table kernels count against it).
-`cpu_baseline` is the CPU oracle, single-threaded, on the same layer.
+step (sum of N*K over the layers * iterations / step time).  `roofline`
+describes the Lloyd-iteration kernel: its average duration is measured with HIP
+events on the launch stream around every fit call inside the timed region (fit
+time / iterations, so launch gaps and the small scale / init / final-table
+kernels count against it).  `cpu_baseline` is the CPU oracle, single-threaded.
 """
 import argparse
 import json
@@ -40,9 +42,9 @@ def bytes_per_weight(g):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="index into the benchmark settings (single-layer ones)")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=1, help="index into the five benchmark settings")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -62,57 +64,76 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = inputs.CONFIGS[args.config]
-    assert len(cfg["layers"]) == 1, "bench.py times the single-layer settings"
-    layer = cfg["layers"][0]
+    big = args.config >= 3
+    steps = args.steps if args.steps is not None else (3 if big else 20)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
     g, fmt, iters = cfg["g"], cfg["fmt"], cfg["iters"]
-    N, K = layer["N"], layer["K"]
-    W = inputs.layer_weights(layer, dev)
-    X = inputs.activations(cfg["xs"][layer["x"]], dev)
     grid = inputs.format_grid(fmt)
+    batch = len(cfg["layers"]) > 2  # the decoder block goes through aaac_fit_batch
 
-    # every buffer is allocated once, outside the timed region
-    I = torch.empty(K, dtype=torch.float32, device=dev)
-    ws_stats = torch.empty(max(A.aaac_act_stats_workspace(X.shape[0], K), 256), dtype=torch.uint8, device=dev)
-    ws_fit = torch.empty(A.aaac_fit_workspace(N, K, g, fmt), dtype=torch.uint8, device=dev)
-    tf = torch.empty(32, dtype=torch.float32, device=dev)
-    tb = torch.empty(32, dtype=torch.int16, device=dev)
-    obj = torch.empty(iters, dtype=torch.float64, device=dev)
-    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
-    scales = torch.empty((N, K // g), dtype=torch.uint8 if fmt == A.NVFP4 else torch.int16, device=dev)
-    What = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+    # inputs and every buffer are created once, outside the timed region
+    Xs = {k: inputs.activations(r, dev) for k, r in cfg["xs"].items()}
+    Is = {k: torch.empty(X.shape[1], dtype=torch.float32, device=dev) for k, X in Xs.items()}
+    ws_stats = {k: torch.empty(max(A.aaac_act_stats_workspace(*X.shape), 256), dtype=torch.uint8, device=dev)
+                for k, X in Xs.items()}
+    layers = []
+    for l in cfg["layers"]:
+        N, K = l["N"], l["K"]
+        layers.append(dict(
+            name=l["name"], N=N, K=K, x=l["x"], W=inputs.layer_weights(l, dev),
+            tf=torch.empty(32, dtype=torch.float32, device=dev), tb=torch.empty(32, dtype=torch.int16, device=dev),
+            obj=torch.empty(iters, dtype=torch.float64, device=dev),
+            codes=torch.empty((N, K // 2), dtype=torch.uint8, device=dev),
+            scales=torch.empty((N, K // g), dtype=torch.uint8 if fmt == A.NVFP4 else torch.int16, device=dev),
+            What=torch.empty((N, K), dtype=torch.bfloat16, device=dev),
+            ws=torch.empty(A.aaac_fit_workspace(N, K, g, fmt), dtype=torch.uint8, device=dev)))
+    if batch:
+        import ctypes
+        arr = (A.binding.aaac_layer_t * len(layers))()
+        for i, L in enumerate(layers):
+            arr[i] = A.binding.aaac_layer_t(L["W"].data_ptr(), L["N"], L["K"], L["W"].stride(0), Is[L["x"]].data_ptr(),
+                                            L["tf"].data_ptr(), L["tb"].data_ptr(), L["obj"].data_ptr())
+        ws_batch = torch.empty(A.aaac_fit_batch_workspace(arr, g, fmt), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    n_w = sum(L["N"] * L["K"] for L in layers)
 
     def step(events=None):
         def mark(i):
             if events is not None:
                 events[i].record(stream)
         mark(0)
-        A.aaac_act_stats(X, I, ws_stats, stream)
+        for k, X in Xs.items():
+            A.aaac_act_stats(X, Is[k], ws_stats[k], stream)
         mark(1)
-        A.aaac_fit(W, g, fmt, I, grid, iters, tf, tb, obj, ws_fit, stream)
+        if batch:
+            A.aaac_fit_batch(arr, g, fmt, grid, iters, ws_batch, stream)
+        else:
+            for L in layers:
+                A.aaac_fit(L["W"], g, fmt, Is[L["x"]], grid, iters, L["tf"], L["tb"], L["obj"], L["ws"], stream)
         mark(2)
-        A.aaac_encode(W, g, fmt, I, tb, codes, scales, stream)
+        for L in layers:
+            A.aaac_encode(L["W"], g, fmt, Is[L["x"]], L["tb"], L["codes"], L["scales"], stream)
         mark(3)
-        A.aaac_dequant(codes, scales, tb, g, fmt, What, stream)
+        for L in layers:
+            A.aaac_dequant(L["codes"], L["scales"], L["tb"], g, fmt, L["What"], stream)
         mark(4)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         step(evs[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
 
     def stage(i):
         return float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs]))
     stats_ms, fit_ms, enc_ms, deq_ms = stage(0), stage(1), stage(2), stage(3)
     iter_us = fit_ms * 1e3 / iters
-    n_w = N * K
     weights_per_s_iter = n_w / (iter_us * 1e-6)
     value = n_w * iters / (ms_per_step * 1e-3)
 
@@ -127,25 +148,27 @@ def main():
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
 
+    x_bytes = sum(X.numel() * 2 for X in Xs.values())
     achieved = LANE_OPS_PER_WEIGHT * weights_per_s_iter / 1e12
     out = {
         "metric": "weights/s per Lloyd iteration (E+M), whole hot path",
         "value": value,
         "unit": "weights/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg["name"], "layer": f"{N}x{K} bf16", "tokens": int(X.shape[0]),
-                   "group_size": g, "format": "nvfp4" if fmt == A.NVFP4 else "int4", "iterations": iters},
+        "config": {"workload": cfg["name"], "layers": [f'{L["name"]} {L["N"]}x{L["K"]} bf16' for L in layers],
+                   "tokens": int(next(iter(Xs.values())).shape[0]), "group_size": g,
+                   "format": "nvfp4" if fmt == A.NVFP4 else "int4", "iterations": iters},
         "layer_fit_ms": fit_ms + enc_ms,
         "stage_ms": {"act_stats": stats_ms, "fit": fit_ms, "encode": enc_ms, "dequant": deq_ms},
-        "act_stats_GBs": X.numel() * 2 / (stats_ms * 1e-3) / 1e9,
+        "act_stats_GBs": x_bytes / (stats_ms * 1e-3) / 1e9,
         "lloyd_iteration_us": iter_us,
         "lloyd_weights_per_s": weights_per_s_iter,
         "roofline": {"bound": "alu", "kernel": "lloyd_iter_kernel", "achieved": achieved,
@@ -157,14 +180,18 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        Wb = inputs.bits(W)
-        Ih = I.cpu().numpy()
+        # bounded sample: the oracle's fit of (a row slice of) the first layer, all iterations
+        L = layers[0]
+        rows = min(L["N"], max(1, int(4.0e8 / (L["K"] * iters))))  # about 20 s at ~50 ns per weight-iteration
+        Wb = inputs.bits(L["W"][:rows])
+        Ih = Is[L["x"]].cpu().numpy()
         t1 = time.perf_counter()
         oracle.fit(Wb, g, fmt, Ih, grid, iters)
         dt = time.perf_counter() - t1
-        out["cpu_baseline"] = {"value": n_w * iters / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
-                               "sample": f"oracle fit of the same {N}x{K} layer, all {iters} iterations, "
-                                         f"{dt:.1f} s on one host core"}
+        out["cpu_baseline"] = {"value": rows * L["K"] * iters / dt, "unit": "weights/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f'oracle fit of {rows} of the {L["N"]} rows of {L["name"]} '
+                                         f'({rows}x{L["K"]}), all {iters} iterations, {dt:.1f} s on one host core'}
     print(json.dumps(out))
 
 
