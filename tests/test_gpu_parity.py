@@ -258,6 +258,51 @@ def test_fit_is_repeatable_and_resumable():
     assert (u16(a[1]) == u16(r[1])).all() and np.allclose(host(a[0]), host(r[0]), rtol=1e-6)
 
 
+def test_whole_path_can_be_captured_in_a_graph_and_replayed():
+    """The library only launches kernels (no memset or memcpy nodes), so a caller may
+    capture it; every replay must give the eager result, also after other work."""
+    N, K, g, fmt, iters = 512, 1024, 16, 0, 4
+    Wt = inputs.make_weight(N, K, "gauss_outlier", 21, DEV)
+    X = inputs.make_activations(256, K, ("gauss", 0.01, "u10_50"), 22, DEV)
+    grid = inputs.format_grid(fmt)
+    I = torch.empty(K, device=DEV)
+    ws_s = torch.empty(max(A.aaac_act_stats_workspace(256, K), 256), dtype=torch.uint8, device=DEV)
+    ws_f = torch.empty(A.aaac_fit_workspace(N, K, g, fmt), dtype=torch.uint8, device=DEV)
+    tf = torch.empty(32, device=DEV)
+    tb = torch.empty(32, dtype=torch.int16, device=DEV)
+    obj = torch.empty(iters, dtype=torch.float64, device=DEV)
+    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=DEV)
+    scales = torch.empty((N, K // g), dtype=torch.uint8, device=DEV)
+    What = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+
+    def run():
+        A.aaac_act_stats(X, I, ws_s)
+        A.aaac_fit(Wt, g, fmt, I, grid, iters, tf, tb, obj, ws_f)
+        A.aaac_encode(Wt, g, fmt, I, tb, codes, scales)
+        A.aaac_dequant(codes, scales, tb, g, fmt, What)
+
+    run()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (I, tb, codes, scales, What)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        for t in (I, tb, codes, scales, What, tf):
+            t.zero_()  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((I, tb, codes, scales, What), want):
+            assert torch.equal(got.view(torch.uint8) if got.dtype == torch.bfloat16 else got,
+                               ref.view(torch.uint8) if ref.dtype == torch.bfloat16 else ref), rep
+
+
 def test_batch_matches_single_calls():
     cfg = inputs.scaled_config(inputs.CONFIGS[3], rows_div=64, tokens_div=512)
     Ws = [inputs.layer_weights(l, DEV) for l in cfg["layers"]]
