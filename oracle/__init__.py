@@ -58,6 +58,10 @@ def lib():
         L.oracle_lloyd_iteration.argtypes = [_P, _I64, _I64, _INT, _P, _P, _P, _P]
         L.oracle_fit.restype = _INT
         L.oracle_fit.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _INT, _P, _P, _P, _P]
+        L.oracle_kmeans_step.restype = _INT
+        L.oracle_kmeans_step.argtypes = [_P, _I64, _I64, _INT, _P, _P, _P]
+        L.oracle_fit_nested.restype = _INT
+        L.oracle_fit_nested.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _INT, _INT, _P, _P, _P, _P]
         L.oracle_encode.restype = _INT
         L.oracle_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P]
         L.oracle_dequant.restype = _INT
@@ -173,6 +177,32 @@ def fit(W_bits, g, fmt, importance, init_grid, iterations, trace=False):
     tt = np.empty((max(iterations, 0), 32), np.float32) if trace else None
     _check(lib().oracle_fit(_ptr(W), N, K, K, g, fmt, _ptr(I), _ptr(G0), iterations, _ptr(tf),
                             _ptr(tb), _ptr(obj), _ptr(tt)), "fit")
+    return dict(tables_f32=tf, tables_bf16=tb, objective=obj, tables_trace=tt)
+
+
+def kmeans_step(wn, g, importance, sigma, tables):
+    """One inner k-means step with the table choice frozen -> new tables f32 [32]."""
+    wn = _c(wn, np.float32)
+    N, K = wn.shape
+    I = _c(importance, np.float32)
+    sg = _c(sigma, np.uint8).reshape(N, K // g)
+    T = _c(tables, np.float32).reshape(32).copy()
+    _check(lib().oracle_kmeans_step(_ptr(wn), N, K, g, _ptr(I), _ptr(sg), _ptr(T)), "kmeans_step")
+    return T
+
+
+def fit_nested(W_bits, g, fmt, importance, init_grid, n_outer, n_inner, trace=False):
+    """Alg. 1 with both loops -> dict(tables_f32, tables_bf16, objective [n_outer], tables_trace)."""
+    W = _c(W_bits, np.uint16)
+    N, K = W.shape
+    I = _c(importance, np.float32)
+    G0 = _c(init_grid, np.float32).reshape(32)
+    tf = np.empty(32, np.float32)
+    tb = np.empty(32, np.uint16)
+    obj = np.empty(max(n_outer, 0), np.float64)
+    tt = np.empty((max(n_outer * n_inner, 0), 32), np.float32) if trace else None
+    _check(lib().oracle_fit_nested(_ptr(W), N, K, K, g, fmt, _ptr(I), _ptr(G0), n_outer, n_inner, _ptr(tf),
+                                   _ptr(tb), _ptr(obj), _ptr(tt)), "fit_nested")
     return dict(tables_f32=tf, tables_bf16=tb, objective=obj, tables_trace=tt)
 
 

@@ -319,6 +319,68 @@ int oracle_fit(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int 
   return 0;
 }
 
+// One step of the inner k-means of Alg. 1 with the table choice frozen: every
+// weight of a group with sigma = r goes to the Voronoi cell of its nearest entry
+// of T_r, and each entry moves to the importance-weighted centroid of its cell
+// (empty cell: keep).  The tables are sorted afterwards; cells are ordered
+// intervals, so this only matters among equal entries.  sigma: [N x K/g].
+int oracle_kmeans_step(const float* wn, int64_t N, int64_t K, int g, const float* importance,
+                       const uint8_t* sigma, float* tables) {
+  if (!valid_shape(N, K, K, g)) return -1;
+  int64_t G = K / g;
+  Sum Swx[32], Sw[32];
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t j = 0; j < G; ++j) {
+      int r = sigma[n * G + j] ? 1 : 0;
+      for (int p = 0; p < g; ++p) {
+        float x = wn[n * K + j * g + p];
+        float I = importance[j * g + p];
+        int b = 16 * r + nearest_index(x, tables + 16 * r);
+        Swx[b].add(static_cast<long double>(I) * static_cast<long double>(x));
+        Sw[b].add(static_cast<long double>(I));
+      }
+    }
+  for (int b = 0; b < 32; ++b) {
+    double num = static_cast<double>(Swx[b].value());
+    double den = static_cast<double>(Sw[b].value());
+    if (den > 0.0) tables[b] = static_cast<float>(num / den);
+  }
+  sort_table(tables);
+  sort_table(tables + 16);
+  return 0;
+}
+
+// Algorithm 1 with both loops: n_outer assignment steps, each followed by
+// n_inner k-means steps on the groups it assigned to each table.
+// objective_trace: [n_outer], the objective seen by each assignment step.
+// tables_trace (optional): the 32 entries after every k-means step,
+// [n_outer * n_inner][32].
+int oracle_fit_nested(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int fmt,
+                      const float* importance, const float* init_grid, int n_outer, int n_inner,
+                      float* tables_f32, uint16_t* tables_bf16, double* objective_trace,
+                      float* tables_trace) {
+  if (!valid_shape(N, K, ldw, g) || n_outer < 0 || n_inner < 1) return -1;
+  std::vector<float> wn(static_cast<size_t>(N) * K);
+  int rc = oracle_normalise(W, N, K, ldw, g, fmt, nullptr, nullptr, wn.data());
+  if (rc) return rc;
+  std::vector<uint8_t> sigma(static_cast<size_t>(N) * (K / g));
+  float T[32];
+  std::memcpy(T, init_grid, sizeof(T));
+  for (int t = 0; t < n_outer; ++t) {
+    double J;
+    oracle_assign(wn.data(), N, K, g, importance, T, nullptr, nullptr, sigma.data(), nullptr, nullptr, &J);
+    if (objective_trace) objective_trace[t] = J;
+    for (int l = 0; l < n_inner; ++l) {
+      oracle_kmeans_step(wn.data(), N, K, g, importance, sigma.data(), T);
+      if (tables_trace) std::memcpy(tables_trace + 32 * (t * n_inner + l), T, sizeof(T));
+    }
+  }
+  if (tables_f32) std::memcpy(tables_f32, T, sizeof(T));
+  if (tables_bf16)
+    for (int b = 0; b < 32; ++b) tables_bf16[b] = f32_to_bf16(T[b]);
+  return 0;
+}
+
 // Final steps of Alg. 1: with the bf16 tables (each still ascending, because
 // rounding is monotone; it can only create ties), recompute sigma per group,
 // write 4-bit nearest-entry indices into the selected table (even k in the low
