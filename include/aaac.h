@@ -108,6 +108,21 @@ int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaa
                    const float* init_grid, int iterations, void* ws, size_t ws_bytes,
                    void* hip_stream);
 
+/* ---- Codebook learning with both loops of the paper's Alg. 1: n_outer assignment
+ * steps (Eq. "selection"), each followed by n_inner k-means steps (Eq.
+ * "kmeans_update") that keep the table choice of the groups fixed: every weight
+ * of a group that chose table r goes to the cell of its nearest entry of the
+ * current T_r, entries move to the weighted centroids (empty cell: keep), and the
+ * tables are sorted after each step.  n_inner = 1 is aaac_fit_batch with
+ * iterations = n_outer.  objective_trace of a layer holds n_outer values (the
+ * objective seen by each assignment step).  n_outer >= 0, n_inner >= 1.  The
+ * workspace query equals aaac_fit_batch_workspace. */
+size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
+                                 aaac_format_t fmt);
+int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
+                    const float* init_grid, int n_outer, int n_inner, void* ws, size_t ws_bytes,
+                    void* hip_stream);
+
 /* ---- Final encode (paper Alg. 1, last four steps; Eq. "aaac_code").  With the
  * bf16 tables (each non-decreasing), recompute sigma per group, write each
  * weight's nearest-entry index into the selected table as a 4-bit code, and the

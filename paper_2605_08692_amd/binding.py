@@ -58,6 +58,10 @@ def library():
         L.aaac_fit_batch_workspace.argtypes = [_P, _INT, _INT, _INT]
         L.aaac_fit_batch.restype = _INT
         L.aaac_fit_batch.argtypes = [_P, _INT, _INT, _INT, _P, _INT, _P, _SZ, _P]
+        L.aaac_fit_nested_workspace.restype = _SZ
+        L.aaac_fit_nested_workspace.argtypes = [_P, _INT, _INT, _INT]
+        L.aaac_fit_nested.restype = _INT
+        L.aaac_fit_nested.argtypes = [_P, _INT, _INT, _INT, _P, _INT, _INT, _P, _SZ, _P]
         L.aaac_encode.restype = _INT
         L.aaac_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P, _P]
         L.aaac_dequant.restype = _INT
@@ -171,6 +175,17 @@ def aaac_fit_batch(layers, group_size, fmt, init_grid, iterations, ws, stream=No
     g = _grid(init_grid)
     _check(library().aaac_fit_batch(layers, len(layers), group_size, fmt, ctypes.c_void_p(g.data_ptr()),
                                     iterations, _dp(ws), ws.numel(), _stream(stream)), "aaac_fit_batch")
+
+
+def aaac_fit_nested_workspace(layers, group_size, fmt):
+    return library().aaac_fit_nested_workspace(layers, len(layers), group_size, fmt)
+
+
+def aaac_fit_nested(layers, group_size, fmt, init_grid, n_outer, n_inner, ws, stream=None):
+    """Both loops of the learning algorithm; layers: array from make_layers (objective: n_outer values)."""
+    g = _grid(init_grid)
+    _check(library().aaac_fit_nested(layers, len(layers), group_size, fmt, ctypes.c_void_p(g.data_ptr()),
+                                     n_outer, n_inner, _dp(ws), ws.numel(), _stream(stream)), "aaac_fit_nested")
 
 
 def aaac_encode(W, group_size, fmt, importance, tables_bf16, codes=None, scales=None, stream=None):

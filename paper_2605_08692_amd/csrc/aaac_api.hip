@@ -112,9 +112,22 @@ size_t aaac_fit_batch_workspace(const aaac_layer_t* layers, int n_layers, int gr
 int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
                    const float* init_grid, int iterations, void* ws, size_t ws_bytes,
                    void* hip_stream) {
+  return aaac_fit_nested(layers, n_layers, group_size, fmt, init_grid, iterations, 1, ws, ws_bytes, hip_stream);
+}
+
+size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
+                                 aaac_format_t fmt) {
+  return aaac_fit_batch_workspace(layers, n_layers, group_size, fmt);
+}
+
+int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
+                    const float* init_grid, int n_outer, int n_inner, void* ws, size_t ws_bytes,
+                    void* hip_stream) {
+  const int iterations = n_outer;
   if (layers == nullptr || init_grid == nullptr) return AAAC_ERR_NULL;
   if (n_layers < 0) return AAAC_ERR_SHAPE;
-  if (!valid_fmt(fmt) || iterations < 0) return AAAC_ERR_ARG;
+  if (!valid_fmt(fmt) || n_outer < 0 || n_inner < 1) return AAAC_ERR_ARG;
+  if ((int64_t)n_outer * n_inner > (int64_t)1 << 30) return AAAC_ERR_ARG;
   if (!valid_group(group_size)) return AAAC_ERR_SHAPE;
   for (int i = 0; i < n_layers; ++i) {
     int rc = check_layer(layers[i], group_size);
@@ -138,7 +151,7 @@ int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaa
       tasks[n] = {l.W, l.N, l.K, l.ldw, l.importance, l.tables_f32, l.tables_bf16, l.objective_trace, base};
       base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size).bytes);
     }
-    if (aaac::launch_fit_group(tasks, n, group_size, fmt, grid, iterations, stream) != hipSuccess)
+    if (aaac::launch_fit_group(tasks, n, group_size, fmt, grid, iterations, n_inner, stream) != hipSuccess)
       return AAAC_ERR_HIP;
   }
   return AAAC_OK;

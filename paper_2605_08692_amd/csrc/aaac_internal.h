@@ -31,7 +31,7 @@ struct FitPlan {
   int rows_per_block;
   int blocks;            // strip_groups * ceil(N / rows_per_block)
   // workspace layout (byte offsets)
-  size_t off_state, off_rinv, bytes;
+  size_t off_state, off_rinv, off_sigma, bytes;
 };
 // cu_budget: compute units this layer may fill (0 = all of the device's).
 FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_budget = 0);
@@ -57,9 +57,11 @@ struct FitTask {
   void* ws;  // this layer's workspace (make_fit_plan(...).bytes)
 };
 constexpr int kMaxFusedLayers = 8;  // layers whose iterations share one launch
-// Fits n <= kMaxFusedLayers layers together: one launch per iteration covers all of them.
+// Fits n <= kMaxFusedLayers layers together: every pass over the weights is one launch that
+// covers all of them.  n_outer assignment passes, each followed by n_inner - 1 passes that
+// only refine the tables with the choice frozen.
 hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
-                            int iterations, hipStream_t stream);
+                            int n_outer, int n_inner, hipStream_t stream);
 hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
                              float* rinv, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);

@@ -13,6 +13,11 @@
 //
 // Nearest entry: the bucket-table search of aaac_search.h.
 //
+// Passes.  A fit is a sequence of passes over the weights, one launch each: an
+// assignment pass (choose the table per group, accumulate the update of both
+// tables) followed by n_inner - 1 refinement passes that keep the choice (stored
+// as one byte per group by the assignment pass) and only search the chosen table.
+//
 // Table update.  sum I*x and sum I of the 32 bins go through fp64 LDS atomics
 // into a block-wide histogram with 32 slots per bin (slot = lane mod 32); each
 // block then adds its 64 sums (and its share of the objective) to a small
@@ -52,6 +57,7 @@ struct LayerArgs {
   const float* rinv;
   const float* importance;
   FitState* state;
+  uint8_t* sigma;         // table choice per group, written by assignment passes (may be null)
   double* objective_trace;
   float* tables_f32;      // outputs of the final kernel
   uint16_t* tables_bf16;
@@ -114,8 +120,13 @@ __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) 
   wave_make_rows(sm.st);
 }
 
-template <int LANES>
-__global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs batch, const int iteration) {
+// pass: index of this pass (selects the accumulator and table buffers);
+// prev_trace: where the objective found in the previous pass's sums goes (-1: nowhere);
+// ASSIGN: assignment pass (true) or refinement pass with the stored choice (false).
+template <int LANES, bool ASSIGN>
+__global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs batch, const int pass,
+                                                                 const int prev_trace) {
+  const int iteration = pass;
   __shared__ LloydLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int li = 0;
@@ -125,6 +136,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   const float* __restrict__ rinv = L.rinv;
   const float* __restrict__ importance = L.importance;
   FitState* __restrict__ state = L.state;
+  uint8_t* __restrict__ sigma_arr = L.sigma;
   double* __restrict__ objective_trace = L.objective_trace;
   const int64_t ldw = L.ldw;
   const int N = L.N, K = L.K, strips = L.strips, strips_per_block = L.strips_per_block,
@@ -160,11 +172,14 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   const float* rbase = rinv + (active ? col / (8 * LANES) : 0);
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
   if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
+  uint8_t* sbase = sigma_arr ? sigma_arr + (active ? col / (8 * LANES) : 0) : nullptr;
   uint4 v_next = make_uint4(0, 0, 0, 0);
   float r_next = 0.0f;
+  uint32_t s_next = 0;  // the stored choice of the next row's group (refinement passes)
   if (active && row < block_r1) {
     v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)row * ldw);
     r_next = rbase[(int64_t)row * G];
+    if (!ASSIGN) s_next = sbase[(int64_t)row * G];
   }
   float Iv[8];
   {
@@ -186,7 +201,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
     wave_make_tables(sm, !first, old_entry);
     if (bid == 0) {
       if (lane < 32 && !first) state->tables[iteration & 1][lane] = sm.st.newtab[lane];
-      if (lane == 32 && !first && objective_trace) objective_trace[iteration - 1] = sm.sums[64];
+      if (lane == 32 && prev_trace >= 0 && objective_trace) objective_trace[prev_trace] = sm.sums[64];
       for (int i = lane; i < kAccCopies * kAccStride; i += 64) (&state->acc[(iteration + 1) % 3][0][0])[i] = 0.0;
     }
   }
@@ -204,6 +219,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   while (row < block_r1) {
     const uint4 v = v_next;
     const float r = r_next;
+    const uint32_t s_cur = s_next;
+    const int cur = row;
     // take the next row of this strip and start its loads before working on this one
     int next = 0;
     if (lane == 0) next = atomicAdd(&sm.st.next_row[queue], 1);
@@ -211,26 +228,46 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
     if (active && next < block_r1) {
       v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)next * ldw);
       r_next = rbase[(int64_t)next * G];
+      if (!ASSIGN) s_next = sbase[(int64_t)next * G];
     }
     row = next;
-    Lane8 a;
-    assign_fast(unpack8(v), r, Iv, sm.st, sm.sl, inv, off, rep4, a);
-    if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm.st, a);
-    const float e0 = group_sum<LANES>(a.p0);
-    const float e1 = group_sum<LANES>(a.p1);
-    const bool sigma = e1 < e0;
-    const uint64_t sigma_mask = __builtin_amdgcn_ballot_w64(sigma);
-    if (active) {
-      const uint32_t slot_up = slot8 + kSlots * 8u;  // same slot, one bin further
+    const uint32_t slot_up = slot8 + kSlots * 8u;  // same slot, one bin further
+    if (ASSIGN) {
+      Lane8 a;
+      assign_fast(unpack8(v), r, Iv, sm.st, sm.sl, inv, off, rep4, a);
+      if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm.st, a);
+      const float e0 = group_sum<LANES>(a.p0);
+      const float e1 = group_sum<LANES>(a.p1);
+      const bool sigma = e1 < e0;
+      const uint64_t sigma_mask = __builtin_amdgcn_ballot_w64(sigma);
+      if (active) {
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const uint32_t k = sigma ? a.k1[p] : a.k0[p];
-        const bool up = __builtin_amdgcn_inverse_ballot_w64((a.m0[p] & ~sigma_mask) | (a.m1[p] & sigma_mask));
-        char* h = hist + (k + (up ? slot_up : slot8));
-        atomicAdd(reinterpret_cast<double*>(h), Id[p] * (double)a.wn[p]);
-        atomicAdd(reinterpret_cast<double*>(h + sizeof(sm.hist[0])), Id[p]);
+        for (int p = 0; p < 8; ++p) {
+          const uint32_t k = sigma ? a.k1[p] : a.k0[p];
+          const bool up = __builtin_amdgcn_inverse_ballot_w64((a.m0[p] & ~sigma_mask) | (a.m1[p] & sigma_mask));
+          char* h = hist + (k + (up ? slot_up : slot8));
+          atomicAdd(reinterpret_cast<double*>(h), Id[p] * (double)a.wn[p]);
+          atomicAdd(reinterpret_cast<double*>(h + sizeof(sm.hist[0])), Id[p]);
+        }
+        if ((lane % LANES) == 0) {
+          obj += (double)(sigma ? e1 : e0);
+          if (sbase) sbase[(int64_t)cur * G] = sigma ? 1 : 0;
+        }
       }
-      if ((lane % LANES) == 0) obj += (double)(sigma ? e1 : e0);
+    } else {
+      Lane8One a;
+      const bool sigma = s_cur != 0;
+      assign_one_fast(unpack8(v), r, sm.st, sm.sl, inv, off, rep4 + (sigma ? (uint32_t)sizeof(sm.sl.lut[0]) : 0u), a);
+      if (__any(a.check != a.check)) assign_one_slow(sm.st, sigma ? 1 : 0, a);
+      if (active) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const bool up = __builtin_amdgcn_inverse_ballot_w64(a.m[p]);
+          char* h = hist + (a.k[p] + (up ? slot_up : slot8));
+          atomicAdd(reinterpret_cast<double*>(h), Id[p] * (double)a.wn[p]);
+          atomicAdd(reinterpret_cast<double*>(h + sizeof(sm.hist[0])), Id[p]);
+        }
+      }
     }
   }
 #pragma unroll
@@ -262,7 +299,10 @@ __global__ void init_state_kernel(const BatchArgs batch, const Grid32 grid) {
 
 // After the last iteration, one block per layer: update the tables from its sums
 // and write the outputs.
-__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchArgs batch, const int iterations) {
+// passes: number of passes that ran; prev_trace as in lloyd_iter_kernel.
+__global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchArgs batch, const int passes,
+                                                                   const int prev_trace) {
+  const int iterations = passes;
   __shared__ LloydLds sm;
   const LayerArgs& L = batch.layer[blockIdx.x];
   FitState* __restrict__ state = L.state;
@@ -279,7 +319,7 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchAr
   if (wave != 0) return;
   wave_make_tables(sm, !none, old_entry);
   __builtin_amdgcn_wave_barrier();
-  if (lane == 32 && !none && L.objective_trace) L.objective_trace[iterations - 1] = sm.sums[64];
+  if (lane == 32 && prev_trace >= 0 && L.objective_trace) L.objective_trace[prev_trace] = sm.sums[64];
   if (lane < 32) {
     const float t = sm.st.newtab[lane];
     if (L.tables_f32) L.tables_f32[lane] = t;
@@ -304,10 +344,18 @@ int compute_units() {
   return cached;
 }
 
+// Index in the objective trace that the sums of pass p carry (-1: none).
+int trace_index(int p, int n_inner) { return p >= 0 && p % n_inner == 0 ? p / n_inner : -1; }
+
 template <int LANES>
-hipError_t launch_iterations(const BatchArgs& batch, int blocks, int iterations, hipStream_t stream) {
-  for (int it = 0; it < iterations; ++it) {
-    lloyd_iter_kernel<LANES><<<blocks, kLloydBlock, 0, stream>>>(batch, it);
+hipError_t launch_passes(const BatchArgs& batch, int blocks, int n_outer, int n_inner, hipStream_t stream) {
+  const int passes = n_outer * n_inner;
+  for (int p = 0; p < passes; ++p) {
+    const int prev_trace = trace_index(p - 1, n_inner);
+    if (p % n_inner == 0)
+      lloyd_iter_kernel<LANES, true><<<blocks, kLloydBlock, 0, stream>>>(batch, p, prev_trace);
+    else
+      lloyd_iter_kernel<LANES, false><<<blocks, kLloydBlock, 0, stream>>>(batch, p, prev_trace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -351,12 +399,15 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_
   auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
   p.off_state = 0;
   p.off_rinv = align(sizeof(FitState));
-  p.bytes = p.off_rinv + align((size_t)(N > 0 ? N : 0) * (K / group_size) * sizeof(float));
+  const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
+  p.off_sigma = p.off_rinv + align(groups * sizeof(float));
+  p.bytes = p.off_sigma + align(groups);
   return p;
 }
 
 hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
-                            int iterations, hipStream_t stream) {
+                            int n_outer, int n_inner, hipStream_t stream) {
+  const int iterations = n_outer;
   if (n <= 0) return hipSuccess;
   // every layer gets its state initialised and its outputs written; only layers
   // that hold weights take part in the iterations
@@ -377,6 +428,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
     a.rinv = reinterpret_cast<const float*>(base + p.off_rinv);
     a.importance = t.importance;
     a.state = reinterpret_cast<FitState*>(base + p.off_state);
+    a.sigma = n_inner > 1 ? reinterpret_cast<uint8_t*>(base + p.off_sigma) : nullptr;
     a.objective_trace = t.objective_trace;
     a.tables_f32 = t.tables_f32;
     a.tables_bf16 = t.tables_bf16;
@@ -405,13 +457,13 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
       if (e != hipSuccess) return e;
     }
     switch (group_size / 8) {
-      case 2: e = launch_iterations<2>(work, blocks, iterations, stream); break;
-      case 4: e = launch_iterations<4>(work, blocks, iterations, stream); break;
-      case 8: e = launch_iterations<8>(work, blocks, iterations, stream); break;
-      default: e = launch_iterations<16>(work, blocks, iterations, stream); break;
+      case 2: e = launch_passes<2>(work, blocks, n_outer, n_inner, stream); break;
+      case 4: e = launch_passes<4>(work, blocks, n_outer, n_inner, stream); break;
+      case 8: e = launch_passes<8>(work, blocks, n_outer, n_inner, stream); break;
+      default: e = launch_passes<16>(work, blocks, n_outer, n_inner, stream); break;
     }
     if (e != hipSuccess) return e;
-    done = iterations;
+    done = n_outer * n_inner;
   }
   // layers without weights: the objective is zero and the tables stay the initial grid
   for (int i = 0; i < n; ++i) {
@@ -422,7 +474,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
     }
   }
   if (work.n > 0) {
-    final_tables_kernel<<<work.n, kLloydBlock, 0, stream>>>(work, done);
+    final_tables_kernel<<<work.n, kLloydBlock, 0, stream>>>(work, done, trace_index(done - 1, n_inner));
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -430,7 +482,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
   for (int i = 0; i < all.n; ++i)
     if (!(all.layer[i].N > 0 && all.layer[i].K > 0)) empty.layer[empty.n++] = all.layer[i];
   if (empty.n > 0) {
-    final_tables_kernel<<<empty.n, kLloydBlock, 0, stream>>>(empty, 0);
+    final_tables_kernel<<<empty.n, kLloydBlock, 0, stream>>>(empty, 0, -1);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -48,7 +48,9 @@ struct alignas(16) SearchTables {
 };
 
 struct alignas(16) SearchLut {
-  uint32_t lut[2][kBuckets * kReplicas];  // per table: 16 * candidate row, replicated
+  // per table: byte offset of the candidate row from row[0][0] (16 * row, plus
+  // sizeof(row[0]) for table 1), replicated
+  uint32_t lut[2][kBuckets * kReplicas];
 };
 
 // Monotone map from a normalised weight to the byte offset of its bucket's
@@ -76,8 +78,7 @@ __device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&
                                             const SearchLut& sl, float inv, float off, uint32_t rep4, Lane8& a) {
   float u0[8], u1[8];
   const char* lut = reinterpret_cast<const char*>(sl.lut);
-  const char* row0 = reinterpret_cast<const char*>(st.row[0]);
-  const char* row1 = reinterpret_cast<const char*>(st.row[1]);
+  const char* rows = reinterpret_cast<const char*>(st.row[0]);
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
     const float wn = x.w[p] * r;
@@ -87,8 +88,8 @@ __device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&
     const uint32_t a1 = *reinterpret_cast<const uint32_t*>(e + sizeof(sl.lut[0]));
     // each row is one 16-byte DS read; all four fields are used, so it is not narrowed
     // (12-byte or split reads of these rows are several times slower)
-    const f32x4 s0 = *reinterpret_cast<const f32x4*>(row0 + a0);
-    const f32x4 s1 = *reinterpret_cast<const f32x4*>(row1 + a1);
+    const f32x4 s0 = *reinterpret_cast<const f32x4*>(rows + a0);
+    const f32x4 s1 = *reinterpret_cast<const f32x4*>(rows + a1);
     const bool c0 = wn > s0.x;
     const bool c1 = wn > s1.x;
     const float d0 = wn - (c0 ? s0.z : s0.y);
@@ -130,6 +131,46 @@ __device__ __forceinline__ void assign_slow(const float (&Iv)[8], const SearchTa
   }
   a.p0 = tree8(u0);
   a.p1 = tree8(u1);
+}
+
+// One table only (r_off = 0 for T0, sizeof(lut[0]) for T1, per lane): bin field of the
+// candidate row, the lane mask of "one higher", and a value that is NaN iff some
+// weight met a poisoned bucket.
+struct Lane8One {
+  float wn[8];
+  uint32_t k[8];
+  uint64_t m[8];
+  float check;
+};
+
+__device__ __forceinline__ void assign_one_fast(const W8& x, float r, const SearchTables& st, const SearchLut& sl,
+                                                float inv, float off, uint32_t rep4_table, Lane8One& a) {
+  const char* lut = reinterpret_cast<const char*>(sl.lut);
+  const char* rows = reinterpret_cast<const char*>(st.row[0]);
+  float check = 0.0f;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const float wn = x.w[p] * r;
+    a.wn[p] = wn;
+    const uint32_t e = *reinterpret_cast<const uint32_t*>(lut + (bucket_row(wn, inv, off) | rep4_table));
+    const f32x4 s = *reinterpret_cast<const f32x4*>(rows + e);
+    a.k[p] = __float_as_uint(s.w);
+    a.m[p] = __builtin_amdgcn_ballot_w64(wn > s.x);
+    check += s.y;  // T[i]; NaN only in the poisoned row
+  }
+  a.check = check;
+}
+
+__device__ __forceinline__ void assign_one_slow(const SearchTables& st, int table, Lane8One& a) {
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const float wn = a.wn[p];
+    int i = 0;
+    for (int j = 0; j < 15; ++j) i += wn > st.row[table][j].thr ? 1 : 0;
+    a.k[p] = st.row[table][i].bin;
+    a.m[p] = 0;
+  }
+  a.check = 0.0f;
 }
 
 // Search rows, bucket map parameters and the bucket of every midpoint from the
@@ -181,7 +222,7 @@ __device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLut& 
         inside += bj == tid ? 1 : 0;
       }
       const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
-      st.entry[r][tid] = 16u * row;
+      st.entry[r][tid] = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
     }
   }
   __syncthreads();

@@ -342,6 +342,80 @@ def test_batch_of_more_layers_than_one_launch_group_and_an_empty_layer():
         assert np.allclose(host(ob)[:iters], ref["objective"], rtol=1e-9)
 
 
+def nested_on_gpu(Ws, Is, g, fmt, grid, n_outer, n_inner):
+    layers, outs = A.make_layers(Ws, Is, n_outer)
+    ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt), dtype=torch.uint8, device=DEV)
+    A.aaac_fit_nested(layers, g, fmt, grid, n_outer, n_inner, ws)
+    torch.cuda.synchronize()
+    return outs
+
+
+@pytest.mark.parametrize("N,K,g,fmt,n_outer,n_inner", [
+    (256, 512, 16, 0, 3, 10),    # the paper's default loop counts on the small benchmark shape
+    (130, 1536, 128, 1, 2, 4),
+    (37, 1040, 16, 0, 2, 3),
+    (64, 640, 32, 1, 3, 2),
+    (96, 1024, 16, 0, 0, 5),     # no outer step: the grid comes back
+])
+def test_nested_loops_match_oracle(N, K, g, fmt, n_outer, n_inner):
+    say(f"[nested] N={N} K={K} g={g} fmt={fmt} outer={n_outer} inner={n_inner}")
+    Wt = inputs.make_weight(N, K, "gauss_outlier", 300 + N + K, DEV)
+    I = oracle.act_stats(inputs.bits(inputs.make_activations(64, K, ("gauss", 0.01, "u10_50"), 310 + K, DEV)))
+    grid = inputs.format_grid(fmt)
+    ref = oracle.fit_nested(inputs.bits(Wt), g, fmt, I, grid, n_outer, n_inner)
+    (tf, tb, ob), = nested_on_gpu([Wt], [torch.from_numpy(I).to(DEV)], g, fmt, grid, n_outer, n_inner)
+    assert (u16(tb) == ref["tables_bf16"]).all()
+    assert tables_close(host(tf), ref["tables_f32"])
+    if n_outer:
+        assert np.allclose(host(ob)[:n_outer], ref["objective"], rtol=1e-9)
+    # and the codes that follow from these tables
+    It = torch.from_numpy(I).to(DEV)
+    codes, scales = A.aaac_encode(Wt, g, fmt, It, tb)
+    torch.cuda.synchronize()
+    rc, rs = oracle.encode(inputs.bits(Wt), g, fmt, I, ref["tables_bf16"])
+    assert (host(codes) == rc).all() and (host(scales).view(rs.dtype) == rs).all()
+
+
+def test_nested_loops_clustered_tables_and_batch():
+    # refinement passes through poisoned buckets, several layers at once, one inner step == plain fit
+    shapes = [(96, 1024), (40, 512), (200, 1536)]
+    g, fmt = 16, 0
+    Ws = [inputs.make_weight(N, K, "student5", 400 + i, DEV) for i, (N, K) in enumerate(shapes)]
+    Is = [torch.rand(K, device=DEV) + 0.05 for _, K in shapes]
+    t0 = inputs.E2M1_GRID.copy()
+    t0[7:10] = [0.0, 0.004, 0.009]
+    t1 = inputs.E2M1_GRID + np.float32(0.25)
+    t1[4:7] = t1[5]
+    grid = np.concatenate([t0, t1]).astype(np.float32)
+    outs = nested_on_gpu(Ws, Is, g, fmt, grid, 2, 3)
+    for W, I, (tf, tb, ob) in zip(Ws, Is, outs):
+        ref = oracle.fit_nested(inputs.bits(W), g, fmt, host(I), grid, 2, 3)
+        assert (u16(tb) == ref["tables_bf16"]).all()
+        assert tables_close(host(tf), ref["tables_f32"])
+        assert np.allclose(host(ob)[:2], ref["objective"], rtol=1e-9)
+    plain = [A.aaac_fit(W, g, fmt, I, inputs.format_grid(fmt), 3) for W, I in zip(Ws, Is)]
+    one = nested_on_gpu(Ws, Is, g, fmt, inputs.format_grid(fmt), 3, 1)
+    torch.cuda.synchronize()
+    for (tf, tb, ob), (pf, pb, po) in zip(one, plain):
+        assert (u16(tb) == u16(pb)).all() and np.allclose(host(tf), host(pf), rtol=1e-6)
+
+
+def test_nested_loops_cfg1_full_size():
+    """The Llama-2-7B-shaped q_proj with the paper's default loop counts (3, 10)."""
+    cfg = inputs.CONFIGS[1]
+    l = cfg["layers"][0]
+    Wt = inputs.layer_weights(l, DEV)
+    I = torch.rand(l["K"], device=DEV) * 100 + 1
+    grid = inputs.format_grid(cfg["fmt"])
+    t0 = time.time()
+    ref = oracle.fit_nested(inputs.bits(Wt), cfg["g"], cfg["fmt"], host(I), grid, 3, 10)
+    say(f"[nested] cfg1 oracle {time.time() - t0:.1f}s")
+    (tf, tb, ob), = nested_on_gpu([Wt], [I], cfg["g"], cfg["fmt"], grid, 3, 10)
+    assert (u16(tb) == ref["tables_bf16"]).all()
+    assert tables_close(host(tf), ref["tables_f32"])
+    assert np.allclose(host(ob)[:3], ref["objective"], rtol=1e-9)
+
+
 # ------------------------------------------ benchmark settings, full size
 
 def test_config0_full():
