@@ -31,6 +31,9 @@ if ROOT not in sys.path:
 # operations (unpack 1, normalise 1, two 4-level searches 16, two table look-ups 2,
 # two error chains 8, selection/bin 1, fp64 accumulate 4).
 LANE_OPS_PER_WEIGHT = 33.0
+# A refinement pass (choice frozen) searches one table and needs no errors: unpack 1,
+# normalise 1, one search 8, bin 1, fp64 accumulate 4.
+LANE_OPS_PER_WEIGHT_REFINE = 15.0
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one op per lane-clock
 HBM_PEAK_GBS = 8000.0
 
@@ -45,6 +48,10 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=1, help="index into the five benchmark settings")
+    ap.add_argument("--n-inner", type=int, default=1,
+                    help="k-means steps per assignment step (Alg. 1's inner loop); above 1 the fit goes through "
+                         "aaac_fit_nested with --n-outer assignment steps")
+    ap.add_argument("--n-outer", type=int, default=None, help="assignment steps when --n-inner > 1 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -69,7 +76,12 @@ def main():
     warmup = args.warmup if args.warmup is not None else (1 if big else 3)
     g, fmt, iters = cfg["g"], cfg["fmt"], cfg["iters"]
     grid = inputs.format_grid(fmt)
-    batch = len(cfg["layers"]) > 2  # the decoder block goes through aaac_fit_batch
+    nested = args.n_inner > 1
+    n_outer = (args.n_outer if args.n_outer is not None else 3) if nested else iters
+    n_inner = args.n_inner
+    iters = n_outer  # length of the objective trace
+    passes = n_outer * n_inner  # passes over the weights per fit
+    batch = len(cfg["layers"]) > 2 or nested  # the decoder block goes through aaac_fit_batch
 
     # inputs and every buffer are created once, outside the timed region
     Xs = {k: inputs.activations(r, dev) for k, r in cfg["xs"].items()}
@@ -93,7 +105,7 @@ def main():
         for i, L in enumerate(layers):
             arr[i] = A.binding.aaac_layer_t(L["W"].data_ptr(), L["N"], L["K"], L["W"].stride(0), Is[L["x"]].data_ptr(),
                                             L["tf"].data_ptr(), L["tb"].data_ptr(), L["obj"].data_ptr())
-        ws_batch = torch.empty(A.aaac_fit_batch_workspace(arr, g, fmt), dtype=torch.uint8, device=dev)
+        ws_batch = torch.empty(A.aaac_fit_nested_workspace(arr, g, fmt), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
     n_w = sum(L["N"] * L["K"] for L in layers)
 
@@ -105,7 +117,9 @@ def main():
         for k, X in Xs.items():
             A.aaac_act_stats(X, Is[k], ws_stats[k], stream)
         mark(1)
-        if batch:
+        if nested:
+            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, n_inner, ws_batch, stream)
+        elif batch:
             A.aaac_fit_batch(arr, g, fmt, grid, iters, ws_batch, stream)
         else:
             for L in layers:
@@ -133,9 +147,30 @@ def main():
     def stage(i):
         return float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs]))
     stats_ms, fit_ms, enc_ms, deq_ms = stage(0), stage(1), stage(2), stage(3)
-    iter_us = fit_ms * 1e3 / iters
+    iter_us = fit_ms * 1e3 / passes
     weights_per_s_iter = n_w / (iter_us * 1e-6)
-    value = n_w * iters / (ms_per_step * 1e-3)
+    value = n_w * passes / (ms_per_step * 1e-3)
+
+    refine = None
+    if nested:
+        # refinement pass alone: the same fit with one inner step costs n_outer assignment passes
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(steps, 3)
+        A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream)
+        e0.record(stream)
+        for _ in range(reps):
+            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        assign_ms = e0.elapsed_time(e1) / reps
+        refine_us = (fit_ms - assign_ms) * 1e3 / (n_outer * (n_inner - 1))
+        ops = LANE_OPS_PER_WEIGHT_REFINE * n_w / (refine_us * 1e-6) / 1e12
+        refine = {"kernel": "lloyd_iter_kernel (choice frozen)", "assign_pass_us": assign_ms * 1e3 / n_outer,
+                  "refine_pass_us": refine_us, "weights_per_s": n_w / (refine_us * 1e-6), "bound": "alu",
+                  "achieved": ops, "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s", "frac": ops / ALU_PEAK_TLANEOPS}
+        # `roofline` below stays the assignment pass
+        iter_us = assign_ms * 1e3 / n_outer
+        weights_per_s_iter = n_w / (iter_us * 1e-6)
 
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -165,7 +200,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["name"], "layers": [f'{L["name"]} {L["N"]}x{L["K"]} bf16' for L in layers],
                    "tokens": int(next(iter(Xs.values())).shape[0]), "group_size": g,
-                   "format": "nvfp4" if fmt == A.NVFP4 else "int4", "iterations": iters},
+                   "format": "nvfp4" if fmt == A.NVFP4 else "int4", "iterations": iters,
+                   "n_inner": n_inner, "passes_per_fit": passes},
         "layer_fit_ms": fit_ms + enc_ms,
         "stage_ms": {"act_stats": stats_ms, "fit": fit_ms, "encode": enc_ms, "dequant": deq_ms},
         "act_stats_GBs": x_bytes / (stats_ms * 1e-3) / 1e9,
@@ -178,20 +214,26 @@ def main():
                      "hbm_frac": bytes_per_weight(g) * weights_per_s_iter / 1e9 / HBM_PEAK_GBS},
     }
 
+    if refine is not None:
+        out["refine_roofline"] = refine
+
     if not args.no_cpu_baseline:
         import oracle
         # bounded sample: the oracle's fit of (a row slice of) the first layer, all iterations
         L = layers[0]
-        rows = min(L["N"], max(1, int(4.0e8 / (L["K"] * iters))))  # about 20 s at ~50 ns per weight-iteration
+        rows = min(L["N"], max(1, int(4.0e8 / (L["K"] * passes))))  # about 20 s at ~50 ns per weight-iteration
         Wb = inputs.bits(L["W"][:rows])
         Ih = Is[L["x"]].cpu().numpy()
         t1 = time.perf_counter()
-        oracle.fit(Wb, g, fmt, Ih, grid, iters)
+        if nested:
+            oracle.fit_nested(Wb, g, fmt, Ih, grid, n_outer, n_inner)
+        else:
+            oracle.fit(Wb, g, fmt, Ih, grid, iters)
         dt = time.perf_counter() - t1
-        out["cpu_baseline"] = {"value": rows * L["K"] * iters / dt, "unit": "weights/s", "cores": 1,
+        out["cpu_baseline"] = {"value": rows * L["K"] * passes / dt, "unit": "weights/s", "cores": 1,
                                "kind": "oracle",
                                "sample": f'oracle fit of {rows} of the {L["N"]} rows of {L["name"]} '
-                                         f'({rows}x{L["K"]}), all {iters} iterations, {dt:.1f} s on one host core'}
+                                         f'({rows}x{L["K"]}), all {passes} passes, {dt:.1f} s on one host core'}
     print(json.dumps(out))
 
 

@@ -97,6 +97,16 @@ def test_other_entry_points_validate():
     assert L.aaac_dequant(FAKE, FAKE, FAKE, 8, 64, 16, 0, FAKE, 63, None) == E_SHAPE
     assert L.aaac_dequant(FAKE, FAKE, FAKE, 8, 64, 16, 3, FAKE, 64, None) == E_ARG
     assert L.aaac_fit_batch(None, 1, 16, 0, FAKE, 1, FAKE, 1 << 20, None) == E_NULL
+    assert L.aaac_fit_nested(None, 1, 16, 0, FAKE, 1, 1, FAKE, 1 << 20, None) == E_NULL
+    layer = A.binding.aaac_layer_t(0x10000, 8, 64, 64, 0x10000, None, 0x10000, None)
+    arr = (A.binding.aaac_layer_t * 1)(layer)
+    grid = np.concatenate([np.arange(16), np.arange(16)]).astype(np.float32)
+    gp = grid.ctypes.data_as(ctypes.c_void_p)
+    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 1, 0, FAKE, 1 << 20, None) == E_ARG    # no inner step
+    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, -1, 2, FAKE, 1 << 20, None) == E_ARG
+    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 1 << 20, 1 << 20, FAKE, 1 << 20, None) == E_ARG  # pass count overflows
+    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 2, 2, FAKE, 16, None) == E_WS
+    assert L.aaac_fit_nested_workspace(arr, 1, 16, 0) == L.aaac_fit_batch_workspace(arr, 1, 16, 0) > 0
 
 
 def test_binding_raises_with_message():
