@@ -62,6 +62,12 @@ def lib():
         L.oracle_kmeans_step.argtypes = [_P, _I64, _I64, _INT, _P, _P, _P]
         L.oracle_fit_nested.restype = _INT
         L.oracle_fit_nested.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _INT, _INT, _P, _P, _P, _P]
+        L.oracle_fit_sel.restype = _INT
+        L.oracle_fit_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _INT, _INT, _P, _P, _P, _P]
+        L.oracle_encode_sel.restype = _INT
+        L.oracle_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64]
+        L.oracle_dequant_sel.restype = _INT
+        L.oracle_dequant_sel.argtypes = [_P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64]
         L.oracle_encode.restype = _INT
         L.oracle_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P]
         L.oracle_dequant.restype = _INT
@@ -228,4 +234,51 @@ def dequant(codes, scales, tables_bf16, g, fmt):
     out = np.empty((N, K), np.uint16)
     _check(lib().oracle_dequant(_ptr(codes), _ptr(scales), _ptr(tb), N, K, g, fmt, _ptr(out), K),
            "dequant")
+    return out
+
+
+# ------------------------------------------- selection groups smaller than scale groups
+
+def fit_sel(W_bits, g, S, fmt, importance, init_grid, n_outer, n_inner, trace=False):
+    """Alg. 1 with scale groups of g and selection groups of S <= g weights."""
+    W = _c(W_bits, np.uint16)
+    N, K = W.shape
+    I = _c(importance, np.float32)
+    G0 = _c(init_grid, np.float32).reshape(32)
+    tf = np.empty(32, np.float32)
+    tb = np.empty(32, np.uint16)
+    obj = np.empty(max(n_outer, 0), np.float64)
+    tt = np.empty((max(n_outer * n_inner, 0), 32), np.float32) if trace else None
+    _check(lib().oracle_fit_sel(_ptr(W), N, K, K, g, S, fmt, _ptr(I), _ptr(G0), n_outer, n_inner, _ptr(tf),
+                                _ptr(tb), _ptr(obj), _ptr(tt)), "fit_sel")
+    return dict(tables_f32=tf, tables_bf16=tb, objective=obj, tables_trace=tt)
+
+
+def sel_stride(K, S):
+    return (K // S + 7) // 8
+
+
+def encode_sel(W_bits, g, S, fmt, importance, tables_bf16):
+    """-> (codes uint8 [N, K/2], scales [N, K/g], sel_bits uint8 [N, ceil(K/S/8)] or None if S == g)."""
+    W = _c(W_bits, np.uint16)
+    N, K = W.shape
+    I = _c(importance, np.float32)
+    tb = _c(tables_bf16, np.uint16).reshape(32)
+    codes = np.empty((N, K // 2), np.uint8)
+    scales = np.empty((N, K // g), _scale_dtype(fmt))
+    bits = np.full((N, sel_stride(K, S)), 0xFF, np.uint8) if S < g else None
+    _check(lib().oracle_encode_sel(_ptr(W), N, K, K, g, S, fmt, _ptr(I), _ptr(tb), _ptr(codes), _ptr(scales),
+                                   _ptr(bits), sel_stride(K, S)), "encode_sel")
+    return codes, scales, bits
+
+
+def dequant_sel(codes, scales, sel_bits, tables_bf16, g, S, fmt):
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape[0], codes.shape[1] * 2
+    scales = _c(scales, _scale_dtype(fmt))
+    tb = _c(tables_bf16, np.uint16).reshape(32)
+    bits = None if sel_bits is None else _c(sel_bits, np.uint8)
+    out = np.empty((N, K), np.uint16)
+    _check(lib().oracle_dequant_sel(_ptr(codes), _ptr(scales), _ptr(bits), 0 if bits is None else bits.shape[1],
+                                    _ptr(tb), N, K, g, S, fmt, _ptr(out), K), "dequant_sel")
     return out

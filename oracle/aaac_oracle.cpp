@@ -2,8 +2,8 @@
 //
 // THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
 // single-threaded C++ restatement of the paper's Algorithm 1 (with
-// n_inner = 1 and caller-supplied initial tables) and of the equations it
-// cites, written so that a reader can check each function against the paper
+// caller-supplied initial tables; one or both loops; selection groups equal to
+// or smaller than the scale groups) and of the equations it cites, written so that a reader can check each function against the paper
 // by eye.  It shares no code, header, table or helper with the HIP library and
 // must only ever be called from tests, from the smoke check and from the
 // benchmark's cpu_baseline leg.
@@ -433,6 +433,121 @@ int oracle_dequant(const uint8_t* codes, const void* scales, const uint16_t* tab
         uint16_t c = static_cast<const uint16_t*>(scales)[n * G + j];
         sigma = c >> 15;
         s = bf16_to_f32(c & 0x7FFF);
+      }
+      uint8_t byte = codes[(n * K + k) / 2];
+      int code = (k & 1) ? (byte >> 4) : (byte & 15);
+      float t = bf16_to_f32(tables_bf16[16 * sigma + code]);
+      W_hat[n * ldo + k] = f32_to_bf16(t * s);
+    }
+  return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Selection groups smaller than scale groups (S < g): every g weights share a
+// scale, every S weights share a table choice (S divides g).  The assignment and
+// k-means steps above act on normalised weights and only know the selection
+// group, so the learning loop is the same with S in place of g after normalising
+// with g.  With S == g this is oracle_fit_nested.
+int oracle_fit_sel(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int S, int fmt,
+                   const float* importance, const float* init_grid, int n_outer, int n_inner,
+                   float* tables_f32, uint16_t* tables_bf16, double* objective_trace,
+                   float* tables_trace) {
+  if (!valid_shape(N, K, ldw, g) || !valid_shape(N, K, ldw, S) || S > g) return -1;
+  if (n_outer < 0 || n_inner < 1) return -1;
+  std::vector<float> wn(static_cast<size_t>(N) * K);
+  int rc = oracle_normalise(W, N, K, ldw, g, fmt, nullptr, nullptr, wn.data());
+  if (rc) return rc;
+  std::vector<uint8_t> sigma(static_cast<size_t>(N) * (K / S));
+  float T[32];
+  std::memcpy(T, init_grid, sizeof(T));
+  for (int t = 0; t < n_outer; ++t) {
+    double J;
+    oracle_assign(wn.data(), N, K, S, importance, T, nullptr, nullptr, sigma.data(), nullptr, nullptr, &J);
+    if (objective_trace) objective_trace[t] = J;
+    for (int l = 0; l < n_inner; ++l) {
+      oracle_kmeans_step(wn.data(), N, K, S, importance, sigma.data(), T);
+      if (tables_trace) std::memcpy(tables_trace + 32 * (t * n_inner + l), T, sizeof(T));
+    }
+  }
+  if (tables_f32) std::memcpy(tables_f32, T, sizeof(T));
+  if (tables_bf16)
+    for (int b = 0; b < 32; ++b) tables_bf16[b] = f32_to_bf16(T[b]);
+  return 0;
+}
+
+// Final steps of Alg. 1 for S <= g.  With S == g sigma goes into the sign bit of
+// the stored scale and sel_bits is not touched.  With S < g the scales stay
+// unsigned and sigma is stored separately, one bit per selection group: group j
+// of row n is bit (j mod 8) of byte n * sel_stride + j / 8, where
+// sel_stride >= ceil(K / S / 8); padding bits of a row's last byte are zero.
+int oracle_encode_sel(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int S, int fmt,
+                      const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
+                      void* scales, uint8_t* sel_bits, int64_t sel_stride) {
+  if (!valid_shape(N, K, ldw, g) || !valid_shape(N, K, ldw, S) || S > g) return -1;
+  if (S < g && (!sel_bits || sel_stride < (K / S + 7) / 8)) return -1;
+  float T[32];
+  for (int b = 0; b < 32; ++b) T[b] = bf16_to_f32(tables_bf16[b]);
+  int64_t G = K / g;
+  float x[128];
+  int i0[128], i1[128];
+  for (int64_t n = 0; n < N; ++n) {
+    if (S < g) std::memset(sel_bits + n * sel_stride, 0, static_cast<size_t>((K / S + 7) / 8));
+    for (int64_t j = 0; j < G; ++j) {
+      const uint16_t* w = W + n * ldw + j * g;
+      float s;
+      uint16_t sc = group_scale(w, g, fmt, &s);
+      float r = 1.0f / s;
+      for (int p = 0; p < g; ++p) x[p] = normalise(w[p], r);
+      int first_sigma = 0;
+      for (int q = 0; q < g / S; ++q) {  // the selection groups inside this scale group
+        float e0 = group_error(x + q * S, importance + j * g + q * S, S, T, i0);
+        float e1 = group_error(x + q * S, importance + j * g + q * S, S, T + 16, i1);
+        int sigma = (e1 < e0) ? 1 : 0;
+        if (q == 0) first_sigma = sigma;
+        const int* idx = sigma ? i1 : i0;
+        for (int p = 0; p < S; p += 2)
+          codes[(n * K + j * g + q * S + p) / 2] = static_cast<uint8_t>(idx[p] | (idx[p + 1] << 4));
+        if (S < g) {
+          int64_t sel = (j * g + q * S) / S;
+          sel_bits[n * sel_stride + sel / 8] |= static_cast<uint8_t>(sigma << (sel % 8));
+        }
+      }
+      int sign = (S == g) ? first_sigma : 0;
+      if (fmt == FMT_NVFP4)
+        static_cast<uint8_t*>(scales)[n * G + j] = static_cast<uint8_t>(sc | (sign << 7));
+      else
+        static_cast<uint16_t*>(scales)[n * G + j] = static_cast<uint16_t>(sc | (sign << 15));
+    }
+  }
+  return 0;
+}
+
+// Dequantisation for S <= g: sigma from the scale's sign bit (S == g) or from the
+// separate bits (S < g, layout as in oracle_encode_sel).
+int oracle_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                       int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K, int g,
+                       int S, int fmt, uint16_t* W_hat, int64_t ldo) {
+  if (!valid_shape(N, K, ldo, g) || !valid_shape(N, K, ldo, S) || S > g) return -1;
+  if (S < g && !sel_bits) return -1;
+  int64_t G = K / g;
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t k = 0; k < K; ++k) {
+      int64_t j = k / g;
+      int sign;
+      float s;
+      if (fmt == FMT_NVFP4) {
+        uint8_t c = static_cast<const uint8_t*>(scales)[n * G + j];
+        sign = c >> 7;
+        s = e4m3_to_f32(c & 0x7F);
+      } else {
+        uint16_t c = static_cast<const uint16_t*>(scales)[n * G + j];
+        sign = c >> 15;
+        s = bf16_to_f32(c & 0x7FFF);
+      }
+      int sigma = sign;
+      if (S < g) {
+        int64_t sel = k / S;
+        sigma = (sel_bits[n * sel_stride + sel / 8] >> (sel % 8)) & 1;
       }
       uint8_t byte = codes[(n * K + k) / 2];
       int code = (k & 1) ? (byte >> 4) : (byte & 15);
