@@ -108,20 +108,23 @@ int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaa
                    const float* init_grid, int iterations, void* ws, size_t ws_bytes,
                    void* hip_stream);
 
-/* ---- Codebook learning with both loops of the paper's Alg. 1: n_outer assignment
- * steps (Eq. "selection"), each followed by n_inner k-means steps (Eq.
- * "kmeans_update") that keep the table choice of the groups fixed: every weight
- * of a group that chose table r goes to the cell of its nearest entry of the
- * current T_r, entries move to the weighted centroids (empty cell: keep), and the
- * tables are sorted after each step.  n_inner = 1 is aaac_fit_batch with
- * iterations = n_outer.  objective_trace of a layer holds n_outer values (the
- * objective seen by each assignment step).  n_outer >= 0, n_inner >= 1.  The
- * workspace query equals aaac_fit_batch_workspace. */
+/* ---- Codebook learning as the paper's Alg. 1 states it in full: both loops and both
+ * granularity parameters ("Granularity parameters": every group_size weights share a
+ * scale, every sel_size weights share a table choice; sel_size is 16, 32, 64 or 128
+ * and divides group_size).  n_outer assignment steps (Eq. "selection", one choice per
+ * sel_size weights), each followed by n_inner k-means steps (Eq. "kmeans_update") that
+ * keep the choices fixed: every weight of a selection group that chose table r goes to
+ * the cell of its nearest entry of the current T_r, entries move to the weighted
+ * centroids (empty cell: keep), and the tables are sorted after each step.
+ * n_inner = 1 with sel_size = group_size is aaac_fit_batch with iterations = n_outer.
+ * objective_trace of a layer holds n_outer values (the objective seen by each
+ * assignment step).  n_outer >= 0, n_inner >= 1.  Errors as aaac_fit; a sel_size that
+ * is not allowed is AAAC_ERR_SHAPE. */
 size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
-                                 aaac_format_t fmt);
-int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
-                    const float* init_grid, int n_outer, int n_inner, void* ws, size_t ws_bytes,
-                    void* hip_stream);
+                                 int sel_size, aaac_format_t fmt);
+int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, int sel_size,
+                    aaac_format_t fmt, const float* init_grid, int n_outer, int n_inner, void* ws,
+                    size_t ws_bytes, void* hip_stream);
 
 /* ---- Final encode (paper Alg. 1, last four steps; Eq. "aaac_code").  With the
  * bf16 tables (each non-decreasing), recompute sigma per group, write each
@@ -140,6 +143,29 @@ int aaac_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size
 int aaac_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16, int64_t N,
                  int64_t K, int group_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
                  void* hip_stream);
+
+/* ---- Encode and dequantisation with selection groups smaller than scale groups
+ * (paper "Granularity parameters"; Alg. 1 last step: the choices are stored in the
+ * sign bits of the scales if sel_size == group_size, separately otherwise, at
+ * 1/sel_size bits per weight).
+ * sel_size == group_size: exactly aaac_encode / aaac_dequant; sel_bits is ignored and
+ * may be NULL.  sel_size < group_size: the stored scales are unsigned (top bit 0) and
+ *   sel_bits   dev u8 [N x sel_stride]: the choice of selection group j of row n
+ *              (columns j*sel_size .. (j+1)*sel_size - 1) is bit (j % 8), counted from
+ *              the least significant, of byte n*sel_stride + j/8; the unused bits of a
+ *              row's last used byte are written as 0; bytes beyond ceil(K/sel_size/8)
+ *              in a row are not touched.
+ *   sel_stride bytes per row, >= ceil(K / sel_size / 8).
+ * Errors as aaac_encode / aaac_dequant; sel_bits NULL when needed is AAAC_ERR_NULL, a
+ * bad sel_size or sel_stride AAAC_ERR_SHAPE. */
+int aaac_encode_sel(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size,
+                    aaac_format_t fmt, const float* importance, const uint16_t* tables_bf16,
+                    uint8_t* codes, void* scales, uint8_t* sel_bits, int64_t sel_stride,
+                    void* hip_stream);
+int aaac_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                     int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K,
+                     int group_size, int sel_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
+                     void* hip_stream);
 
 #ifdef __cplusplus
 }

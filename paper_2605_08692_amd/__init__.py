@@ -6,7 +6,8 @@ The functions re-exported here only marshal arguments into that library; they
 raise if it has not been built.
 """
 from .binding import (  # noqa: F401
-    AaacError, aaac_act_stats, aaac_act_stats_workspace, aaac_dequant, aaac_encode, aaac_fit,
-    aaac_fit_batch, aaac_fit_batch_workspace, aaac_fit_nested, aaac_fit_nested_workspace, aaac_fit_workspace, library, library_path, make_layers,
+    AaacError, aaac_act_stats, aaac_act_stats_workspace, aaac_dequant, aaac_dequant_sel, aaac_encode,
+    aaac_encode_sel, aaac_fit, aaac_fit_batch, aaac_fit_batch_workspace, aaac_fit_nested,
+    aaac_fit_nested_workspace, aaac_fit_workspace, library, library_path, make_layers, sel_stride,
     NVFP4, INT4,
 )

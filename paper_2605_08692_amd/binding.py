@@ -59,9 +59,13 @@ def library():
         L.aaac_fit_batch.restype = _INT
         L.aaac_fit_batch.argtypes = [_P, _INT, _INT, _INT, _P, _INT, _P, _SZ, _P]
         L.aaac_fit_nested_workspace.restype = _SZ
-        L.aaac_fit_nested_workspace.argtypes = [_P, _INT, _INT, _INT]
+        L.aaac_fit_nested_workspace.argtypes = [_P, _INT, _INT, _INT, _INT]
         L.aaac_fit_nested.restype = _INT
-        L.aaac_fit_nested.argtypes = [_P, _INT, _INT, _INT, _P, _INT, _INT, _P, _SZ, _P]
+        L.aaac_fit_nested.argtypes = [_P, _INT, _INT, _INT, _INT, _P, _INT, _INT, _P, _SZ, _P]
+        L.aaac_encode_sel.restype = _INT
+        L.aaac_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64, _P]
+        L.aaac_dequant_sel.restype = _INT
+        L.aaac_dequant_sel.argtypes = [_P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64, _P]
         L.aaac_encode.restype = _INT
         L.aaac_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P, _P]
         L.aaac_dequant.restype = _INT
@@ -177,15 +181,17 @@ def aaac_fit_batch(layers, group_size, fmt, init_grid, iterations, ws, stream=No
                                     iterations, _dp(ws), ws.numel(), _stream(stream)), "aaac_fit_batch")
 
 
-def aaac_fit_nested_workspace(layers, group_size, fmt):
-    return library().aaac_fit_nested_workspace(layers, len(layers), group_size, fmt)
+def aaac_fit_nested_workspace(layers, group_size, fmt, sel_size=None):
+    return library().aaac_fit_nested_workspace(layers, len(layers), group_size, sel_size or group_size, fmt)
 
 
-def aaac_fit_nested(layers, group_size, fmt, init_grid, n_outer, n_inner, ws, stream=None):
-    """Both loops of the learning algorithm; layers: array from make_layers (objective: n_outer values)."""
+def aaac_fit_nested(layers, group_size, fmt, init_grid, n_outer, n_inner, ws, stream=None, sel_size=None):
+    """Both loops of the learning algorithm, one table choice per sel_size weights (default: per
+    scale group); layers: array from make_layers (objective: n_outer values)."""
     g = _grid(init_grid)
-    _check(library().aaac_fit_nested(layers, len(layers), group_size, fmt, ctypes.c_void_p(g.data_ptr()),
-                                     n_outer, n_inner, _dp(ws), ws.numel(), _stream(stream)), "aaac_fit_nested")
+    _check(library().aaac_fit_nested(layers, len(layers), group_size, sel_size or group_size, fmt,
+                                     ctypes.c_void_p(g.data_ptr()), n_outer, n_inner, _dp(ws), ws.numel(),
+                                     _stream(stream)), "aaac_fit_nested")
 
 
 def aaac_encode(W, group_size, fmt, importance, tables_bf16, codes=None, scales=None, stream=None):
@@ -210,4 +216,41 @@ def aaac_dequant(codes, scales, tables_bf16, group_size, fmt, W_hat=None, stream
     ldo = W_hat.stride(0) if N > 1 else max(W_hat.stride(0), K)
     _check(library().aaac_dequant(_dp(codes), _dp(scales), _dp(tables_bf16), N, K, group_size, fmt,
                                   _dp(W_hat), ldo, _stream(stream)), "aaac_dequant")
+    return W_hat
+
+
+def sel_stride(K, sel_size):
+    """Bytes per row of the separate selection bits."""
+    return (K // sel_size + 7) // 8
+
+
+def aaac_encode_sel(W, group_size, sel_size, fmt, importance, tables_bf16, codes=None, scales=None,
+                    sel_bits=None, stream=None):
+    """-> (codes, scales, sel_bits uint8 [N, ceil(K/sel_size/8)] or None when sel_size == group_size)."""
+    assert W.dtype == torch.bfloat16 and W.dim() == 2 and W.stride(1) == 1
+    N, K = W.shape
+    if codes is None:
+        codes = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty((N, K // group_size), dtype=_scale_dtype(fmt), device=W.device)
+    if sel_bits is None and sel_size < group_size:
+        sel_bits = torch.empty((N, sel_stride(K, sel_size)), dtype=torch.uint8, device=W.device)
+    ldw = W.stride(0) if N > 1 else max(W.stride(0), K)
+    stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
+    _check(library().aaac_encode_sel(_dp(W), N, K, ldw, group_size, sel_size, fmt, _dp(importance),
+                                     _dp(tables_bf16), _dp(codes), _dp(scales), _dp(sel_bits), stride,
+                                     _stream(stream)), "aaac_encode_sel")
+    return codes, scales, sel_bits
+
+
+def aaac_dequant_sel(codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, W_hat=None, stream=None):
+    """-> W_hat bf16 [N, K]."""
+    N, K = codes.shape[0], codes.shape[1] * 2
+    if W_hat is None:
+        W_hat = torch.empty((N, K), dtype=torch.bfloat16, device=codes.device)
+    ldo = W_hat.stride(0) if N > 1 else max(W_hat.stride(0), K)
+    stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
+    _check(library().aaac_dequant_sel(_dp(codes), _dp(scales), _dp(sel_bits), stride, _dp(tables_bf16), N, K,
+                                      group_size, sel_size, fmt, _dp(W_hat), ldo, _stream(stream)),
+           "aaac_dequant_sel")
     return W_hat

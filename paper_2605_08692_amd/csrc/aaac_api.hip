@@ -23,6 +23,11 @@ int check_matrix(const void* p, int64_t N, int64_t K, int64_t ld, int group_size
   return AAAC_OK;
 }
 
+// sel_size: 16..128 and a divisor of the scale group size.
+bool valid_sel(int sel_size, int group_size) {
+  return valid_group(sel_size) && sel_size <= group_size && group_size % sel_size == 0;
+}
+
 int check_grid(const float* g) {
   for (int i = 0; i < 32; ++i)
     if (!std::isfinite(g[i])) return AAAC_ERR_ARG;
@@ -86,7 +91,7 @@ int aaac_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float*
 
 size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt) {
   if (N < 0 || K < 0 || !valid_group(group_size) || !valid_fmt(fmt) || K % group_size != 0) return 0;
-  return aaac::make_fit_plan(N, K, K, group_size).bytes;
+  return aaac::make_fit_plan(N, K, K, group_size, group_size).bytes;
 }
 
 int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
@@ -99,59 +104,60 @@ int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, a
 
 size_t aaac_fit_batch_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
                                 aaac_format_t fmt) {
-  if (layers == nullptr || n_layers < 0) return 0;
-  size_t total = 0;
-  for (int i = 0; i < n_layers; ++i) {
-    size_t b = aaac_fit_workspace(layers[i].N, layers[i].K, group_size, fmt);
-    if (b == 0) return 0;
-    total += align256(b);
-  }
-  return total;
+  return aaac_fit_nested_workspace(layers, n_layers, group_size, group_size, fmt);
 }
 
 int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
                    const float* init_grid, int iterations, void* ws, size_t ws_bytes,
                    void* hip_stream) {
-  return aaac_fit_nested(layers, n_layers, group_size, fmt, init_grid, iterations, 1, ws, ws_bytes, hip_stream);
+  return aaac_fit_nested(layers, n_layers, group_size, group_size, fmt, init_grid, iterations, 1, ws, ws_bytes,
+                         hip_stream);
 }
 
 size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
-                                 aaac_format_t fmt) {
-  return aaac_fit_batch_workspace(layers, n_layers, group_size, fmt);
+                                 int sel_size, aaac_format_t fmt) {
+  if (layers == nullptr || n_layers < 0) return 0;
+  if (!valid_group(group_size) || !valid_sel(sel_size, group_size) || !valid_fmt(fmt)) return 0;
+  size_t total = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    const int64_t N = layers[i].N, K = layers[i].K;
+    if (N < 0 || K < 0 || K % group_size != 0) return 0;
+    total += align256(aaac::make_fit_plan(N, K, K, group_size, sel_size).bytes);
+  }
+  return total;
 }
 
-int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
-                    const float* init_grid, int n_outer, int n_inner, void* ws, size_t ws_bytes,
-                    void* hip_stream) {
-  const int iterations = n_outer;
+int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, int sel_size,
+                    aaac_format_t fmt, const float* init_grid, int n_outer, int n_inner, void* ws,
+                    size_t ws_bytes, void* hip_stream) {
   if (layers == nullptr || init_grid == nullptr) return AAAC_ERR_NULL;
   if (n_layers < 0) return AAAC_ERR_SHAPE;
   if (!valid_fmt(fmt) || n_outer < 0 || n_inner < 1) return AAAC_ERR_ARG;
   if ((int64_t)n_outer * n_inner > (int64_t)1 << 30) return AAAC_ERR_ARG;
-  if (!valid_group(group_size)) return AAAC_ERR_SHAPE;
+  if (!valid_group(group_size) || !valid_sel(sel_size, group_size)) return AAAC_ERR_SHAPE;
   for (int i = 0; i < n_layers; ++i) {
     int rc = check_layer(layers[i], group_size);
     if (rc) return rc;
   }
   int rc = check_grid(init_grid);
   if (rc) return rc;
-  rc = check_ws(ws, ws_bytes, aaac_fit_batch_workspace(layers, n_layers, group_size, fmt));
+  rc = check_ws(ws, ws_bytes, aaac_fit_nested_workspace(layers, n_layers, group_size, sel_size, fmt));
   if (rc) return rc;
 
   aaac::Grid32 grid;
   for (int i = 0; i < 32; ++i) grid.t[i] = init_grid[i];
   char* base = static_cast<char*>(ws);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // the layers are fitted in groups whose iterations share one launch each
+  // the layers are fitted in groups whose passes share one launch each
   for (int first = 0; first < n_layers; first += aaac::kMaxFusedLayers) {
     aaac::FitTask tasks[aaac::kMaxFusedLayers];
     int n = 0;
     for (int i = first; i < n_layers && n < aaac::kMaxFusedLayers; ++i, ++n) {
       const aaac_layer_t& l = layers[i];
       tasks[n] = {l.W, l.N, l.K, l.ldw, l.importance, l.tables_f32, l.tables_bf16, l.objective_trace, base};
-      base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size).bytes);
+      base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size, sel_size).bytes);
     }
-    if (aaac::launch_fit_group(tasks, n, group_size, fmt, grid, iterations, n_inner, stream) != hipSuccess)
+    if (aaac::launch_fit_group(tasks, n, group_size, sel_size, fmt, grid, n_outer, n_inner, stream) != hipSuccess)
       return AAAC_ERR_HIP;
   }
   return AAAC_OK;
@@ -160,27 +166,53 @@ int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, aa
 int aaac_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
                 const float* importance, const uint16_t* tables_bf16, uint8_t* codes, void* scales,
                 void* hip_stream) {
-  if (importance == nullptr || tables_bf16 == nullptr) return AAAC_ERR_NULL;
-  if (N > 0 && (W == nullptr || codes == nullptr || scales == nullptr)) return AAAC_ERR_NULL;
-  int rc = check_matrix(W, N, K, ldw, group_size);
-  if (rc) return rc;
-  if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
-  if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(importance, 16)) return AAAC_ERR_SHAPE;
-  return from_hip(aaac::launch_encode(W, N, K, ldw, group_size, fmt, importance, tables_bf16, codes,
-                                      scales, static_cast<hipStream_t>(hip_stream)));
+  return aaac_encode_sel(W, N, K, ldw, group_size, group_size, fmt, importance, tables_bf16, codes, scales,
+                         nullptr, 0, hip_stream);
 }
 
 int aaac_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16, int64_t N,
                  int64_t K, int group_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
                  void* hip_stream) {
+  return aaac_dequant_sel(codes, scales, nullptr, 0, tables_bf16, N, K, group_size, group_size, fmt, W_hat, ldo,
+                          hip_stream);
+}
+
+int aaac_encode_sel(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size,
+                    aaac_format_t fmt, const float* importance, const uint16_t* tables_bf16,
+                    uint8_t* codes, void* scales, uint8_t* sel_bits, int64_t sel_stride,
+                    void* hip_stream) {
+  if (importance == nullptr || tables_bf16 == nullptr) return AAAC_ERR_NULL;
+  if (N > 0 && (W == nullptr || codes == nullptr || scales == nullptr)) return AAAC_ERR_NULL;
+  int rc = check_matrix(W, N, K, ldw, group_size);
+  if (rc) return rc;
+  if (!valid_sel(sel_size, group_size)) return AAAC_ERR_SHAPE;
+  if (sel_size < group_size) {
+    if (N > 0 && sel_bits == nullptr) return AAAC_ERR_NULL;
+    if (sel_stride < (K / sel_size + 7) / 8) return AAAC_ERR_SHAPE;
+  }
+  if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
+  if (!aligned(codes, 4) || !aligned(scales, 2) || !aligned(importance, 16)) return AAAC_ERR_SHAPE;
+  return from_hip(aaac::launch_encode(W, N, K, ldw, group_size, sel_size, fmt, importance, tables_bf16, codes,
+                                      scales, sel_bits, sel_stride, static_cast<hipStream_t>(hip_stream)));
+}
+
+int aaac_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                     int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K,
+                     int group_size, int sel_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
+                     void* hip_stream) {
   if (tables_bf16 == nullptr) return AAAC_ERR_NULL;
   if (N > 0 && (codes == nullptr || scales == nullptr || W_hat == nullptr)) return AAAC_ERR_NULL;
   int rc = check_matrix(W_hat, N, K, ldo, group_size);
   if (rc) return rc;
+  if (!valid_sel(sel_size, group_size)) return AAAC_ERR_SHAPE;
+  if (sel_size < group_size) {
+    if (N > 0 && sel_bits == nullptr) return AAAC_ERR_NULL;
+    if (sel_stride < (K / sel_size + 7) / 8) return AAAC_ERR_SHAPE;
+  }
   if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
   if (!aligned(codes, 4) || !aligned(scales, 2)) return AAAC_ERR_SHAPE;
-  return from_hip(aaac::launch_dequant(codes, scales, tables_bf16, N, K, group_size, fmt, W_hat, ldo,
-                                       static_cast<hipStream_t>(hip_stream)));
+  return from_hip(aaac::launch_dequant(codes, scales, sel_bits, sel_stride, tables_bf16, N, K, group_size,
+                                       sel_size, fmt, W_hat, ldo, static_cast<hipStream_t>(hip_stream)));
 }
 
 }  // extern "C"

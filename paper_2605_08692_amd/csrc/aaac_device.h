@@ -70,6 +70,15 @@ __device__ __forceinline__ float group_max(float v) {
   if (LANES >= 16) v = fmaxf(v, dpp<kDppMirror>(v));
   return v;
 }
+// The same with the group width known only at run time (2, 4, 8 or 16 lanes, wavefront-uniform).
+__device__ __forceinline__ float group_max_lanes(float v, int lanes) {
+  v = fmaxf(v, dpp<kDppXor1>(v));
+  if (lanes >= 4) v = fmaxf(v, dpp<kDppXor2>(v));
+  if (lanes >= 8) v = fmaxf(v, dpp<kDppHalfMirror>(v));
+  if (lanes >= 16) v = fmaxf(v, dpp<kDppMirror>(v));
+  return v;
+}
+
 
 // Eight bf16 weights held by one lane.
 struct W8 {

@@ -24,7 +24,8 @@ struct FitState {
 // rectangle of `strips_per_block` 512-column strips x `rows_per_block` rows.
 struct FitPlan {
   int64_t N, K, ldw;
-  int group_size;
+  int group_size;        // weights that share a scale
+  int sel_size;          // weights that share a table choice (divides group_size)
   int strips;            // ceil(K / 512)
   int strips_per_block;  // 1, 2, 4, 8 or 16 (wavefront w works on strip w % strips_per_block)
   int strip_groups;      // ceil(strips / strips_per_block)
@@ -34,7 +35,7 @@ struct FitPlan {
   size_t off_state, off_rinv, off_sigma, bytes;
 };
 // cu_budget: compute units this layer may fill (0 = all of the device's).
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_budget = 0);
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cu_budget = 0);
 
 struct StatsPlan {
   int strips;             // column groups of 4096
@@ -60,16 +61,19 @@ constexpr int kMaxFusedLayers = 8;  // layers whose iterations share one launch
 // Fits n <= kMaxFusedLayers layers together: every pass over the weights is one launch that
 // covers all of them.  n_outer assignment passes, each followed by n_inner - 1 passes that
 // only refine the tables with the choice frozen.
-hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
-                            int n_outer, int n_inner, hipStream_t stream);
+hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel_size, int fmt,
+                            const Grid32& grid, int n_outer, int n_inner, hipStream_t stream);
 hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
                              float* rinv, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
-hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
-                         const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
-                         void* scales, hipStream_t stream);
-hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16,
-                          int64_t N, int64_t K, int group_size, int fmt, void* W_hat, int64_t ldo,
+// sel_bits: the separate selection bits (row stride sel_stride bytes) when sel_size < group_size,
+// null when the choice lives in the sign bit of the scale (sel_size == group_size).
+hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size,
+                         int fmt, const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
+                         void* scales, uint8_t* sel_bits, int64_t sel_stride, hipStream_t stream);
+hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                          int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K,
+                          int group_size, int sel_size, int fmt, void* W_hat, int64_t ldo,
                           hipStream_t stream);
 
 }  // namespace aaac

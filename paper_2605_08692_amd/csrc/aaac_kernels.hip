@@ -160,13 +160,17 @@ struct alignas(16) EncodeLds {
 };
 
 // Same block / wavefront / row mapping and the same bucket-table search as the
-// Lloyd iteration; per row a lane recomputes its group's scale, takes both
-// errors, and writes 8 codes as one 32-bit store (the first lane of a group also
-// stores the scale with the selection bit).
+// Lloyd iteration; per row a lane recomputes its scale group's scale, takes both
+// errors of its selection group, and writes 8 codes as one 32-bit store.  The
+// first lane of a scale group stores the scale; the table choice goes into the
+// scale's top bit when both groups coincide (sel_bits null), otherwise into the
+// separate bit array: selection group j of a row is bit j % 8 of byte j / 8.
+// LANES: lanes per selection group; scale_lanes: lanes per scale group.
 template <int LANES, int FMT>
 __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     const uint16_t* __restrict__ W, int N, int K, int64_t ldw, const float* __restrict__ importance,
     const uint16_t* __restrict__ tables_bf16, uint8_t* __restrict__ codes, void* __restrict__ scales,
+    uint8_t* __restrict__ sel_bits, int64_t sel_stride, int scale_lanes,
     int strips, int strips_per_block, int strip_groups, int rows_per_block) {
   __shared__ EncodeLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -182,7 +186,13 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
   const int col = strip * kStripCols + lane * 8;
   const bool has_strip = strip < strips;
   const bool active = has_strip && col < K;
-  const int G = K / (8 * LANES);
+  const int Gs = K / (8 * scale_lanes);  // scale groups per row
+  // selection bits: a wavefront's strip holds 64 / LANES groups = 8 / LANES bytes; lane b builds byte b
+  constexpr int kSelBytes = LANES <= 8 ? 8 / LANES : 1;
+  const int sel_lane = lane & (kSelBytes - 1);
+  const int sel_byte = strip * kSelBytes + sel_lane;             // byte index inside the row
+  const bool sel_writer = sel_bits != nullptr && has_strip && lane < kSelBytes &&
+                          (int64_t)sel_byte * 64 * LANES < K;   // the byte's first group starts inside the row
   const uint16_t* wbase = W + (active ? col : 0);
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
   if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
@@ -212,14 +222,14 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     row = next;
     const W8 x = unpack8(v);
     float s;
-    const uint32_t sc = scale_code<FMT>(group_max<LANES>(absmax8(x)), &s);
+    const uint32_t sc = scale_code<FMT>(group_max_lanes(absmax8(x), scale_lanes), &s);
     const float r = div_rn(1.0f, s);
     Lane8 a;
     assign_fast(x, r, Iv, sm.st, sm.sl, inv, off, rep4, a);
     if (__any((a.p0 != a.p0) || (a.p1 != a.p1))) assign_slow(Iv, sm.st, a);
     const float e0 = group_sum<LANES>(a.p0);
     const float e1 = group_sum<LANES>(a.p1);
-    const bool sigma = e1 < e0;
+    const bool sigma = active && e1 < e0;
     const uint64_t sigma_mask = __builtin_amdgcn_ballot_w64(sigma);
     uint32_t packed = 0;
 #pragma unroll
@@ -231,20 +241,31 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     }
     if (active) {
       *reinterpret_cast<uint32_t*>(codes + ((int64_t)cur * K + col) / 2) = packed;
-      if ((lane % LANES) == 0) {
-        const int64_t g = (int64_t)cur * G + col / (8 * LANES);
-        if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sigma ? 0x80u : 0u));
-        else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sigma ? 0x8000u : 0u));
+      if ((lane % scale_lanes) == 0) {
+        const int64_t g = (int64_t)cur * Gs + col / (8 * scale_lanes);
+        const bool sign = sel_bits == nullptr && sigma;
+        if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sign ? 0x80u : 0u));
+        else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sign ? 0x8000u : 0u));
       }
+    }
+    if (sel_writer) {  // bit i of this lane's byte: the choice of the group led by lane (8 * sel_lane + i) * LANES
+      uint32_t byte = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        byte |= (uint32_t)((sigma_mask >> (((8 * sel_lane + i) * LANES) & 63)) & 1u) << i;
+      sel_bits[(int64_t)cur * sel_stride + sel_byte] = (uint8_t)byte;
     }
   }
 }
 
 // ---------------------------------------------------------------- dequant
 
+// sel_bits null: the table choice is the top bit of the scale; otherwise bit j % 8 of byte
+// j / 8 of the row's sel_stride bytes, j = column / sel_size.
 template <int FMT>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(
     const uint8_t* __restrict__ codes, const void* __restrict__ scales,
+    const uint8_t* __restrict__ sel_bits, int64_t sel_stride, int sel_size,
     const uint16_t* __restrict__ tables_bf16, int64_t N, int64_t K, int group_size,
     uint16_t* __restrict__ W_hat, int64_t ldo) {
   __shared__ float sT[32];
@@ -265,6 +286,10 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(
     sc = static_cast<const uint16_t*>(scales)[g];
     sigma = sc >> 15;
     s = __uint_as_float((sc & 0x7FFFu) << 16);
+  }
+  if (sel_bits != nullptr) {
+    const int64_t j = col / sel_size;
+    sigma = (sel_bits[row * sel_stride + (j >> 3)] >> (j & 7)) & 1u;
   }
   const uint32_t packed = *reinterpret_cast<const uint32_t*>(codes + (row * K + col) / 2);
   const float* T = sT + 16 * sigma;
@@ -360,46 +385,61 @@ hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, i
 
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) { return fill_zero(p, bytes, stream); }
 
+struct EncodeCall {
+  const uint16_t* W;
+  int64_t N, K, ldw;
+  int group_size, fmt;
+  const float* importance;
+  const uint16_t* tables_bf16;
+  uint8_t* codes;
+  void* scales;
+  uint8_t* sel_bits;
+  int64_t sel_stride;
+};
+
 template <int LANES>
-static hipError_t launch_encode_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt,
-                                      const float* importance, const uint16_t* tables_bf16,
-                                      uint8_t* codes, void* scales, hipStream_t stream) {
-  const FitPlan p = make_fit_plan(N, K, ldw, 8 * LANES);
-  if (fmt == 0)
-    encode_kernel<LANES, 0><<<p.blocks, kSearchBlock, 0, stream>>>(W, (int)N, (int)K, ldw, importance, tables_bf16,
-                                                                  codes, scales, p.strips, p.strips_per_block,
-                                                                  p.strip_groups, p.rows_per_block);
+static hipError_t launch_encode_lanes(const EncodeCall& c, hipStream_t stream) {
+  const FitPlan p = make_fit_plan(c.N, c.K, c.ldw, c.group_size, 8 * LANES);
+  if (c.fmt == 0)
+    encode_kernel<LANES, 0><<<p.blocks, kSearchBlock, 0, stream>>>(
+        c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride,
+        c.group_size / 8, p.strips, p.strips_per_block, p.strip_groups, p.rows_per_block);
   else
-    encode_kernel<LANES, 1><<<p.blocks, kSearchBlock, 0, stream>>>(W, (int)N, (int)K, ldw, importance, tables_bf16,
-                                                                  codes, scales, p.strips, p.strips_per_block,
-                                                                  p.strip_groups, p.rows_per_block);
+    encode_kernel<LANES, 1><<<p.blocks, kSearchBlock, 0, stream>>>(
+        c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride,
+        c.group_size / 8, p.strips, p.strips_per_block, p.strip_groups, p.rows_per_block);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }
 
-hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
-                         const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
-                         void* scales, hipStream_t stream) {
+hipError_t launch_encode(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size,
+                         int fmt, const float* importance, const uint16_t* tables_bf16, uint8_t* codes,
+                         void* scales, uint8_t* sel_bits, int64_t sel_stride, hipStream_t stream) {
   if (N == 0 || K == 0) return hipSuccess;
-  const uint16_t* Wp = static_cast<const uint16_t*>(W);
-  switch (group_size / 8) {
-    case 2: return launch_encode_lanes<2>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
-    case 4: return launch_encode_lanes<4>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
-    case 8: return launch_encode_lanes<8>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
-    default: return launch_encode_lanes<16>(Wp, N, K, ldw, fmt, importance, tables_bf16, codes, scales, stream);
+  const EncodeCall c = {static_cast<const uint16_t*>(W), N, K, ldw, group_size, fmt, importance, tables_bf16,
+                        codes, scales, sel_size < group_size ? sel_bits : nullptr, sel_stride};
+  switch (sel_size / 8) {
+    case 2: return launch_encode_lanes<2>(c, stream);
+    case 4: return launch_encode_lanes<4>(c, stream);
+    case 8: return launch_encode_lanes<8>(c, stream);
+    default: return launch_encode_lanes<16>(c, stream);
   }
 }
 
-hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint16_t* tables_bf16,
-                          int64_t N, int64_t K, int group_size, int fmt, void* W_hat, int64_t ldo,
+hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                          int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K,
+                          int group_size, int sel_size, int fmt, void* W_hat, int64_t ldo,
                           hipStream_t stream) {
   if (N == 0 || K == 0) return hipSuccess;
   const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
   uint16_t* out = static_cast<uint16_t*>(W_hat);
+  const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   if (fmt == 0)
-    dequant_kernel<0><<<gblocks, kBlock, 0, stream>>>(codes, scales, tables_bf16, N, K, group_size, out, ldo);
+    dequant_kernel<0><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, N, K,
+                                                      group_size, out, ldo);
   else
-    dequant_kernel<1><<<gblocks, kBlock, 0, stream>>>(codes, scales, tables_bf16, N, K, group_size, out, ldo);
+    dequant_kernel<1><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, N, K,
+                                                      group_size, out, ldo);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }

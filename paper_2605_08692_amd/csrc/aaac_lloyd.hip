@@ -6,8 +6,9 @@
 // bound to one strip (64 lanes x 8 bf16; a lane keeps the importances of its 8
 // columns in registers) and takes rows of that strip one at a time from a
 // counter in LDS, so all wavefronts of a block finish together whatever order
-// the hardware favours them in.  A group of g weights is held by g/8 adjacent
-// lanes.  Up to eight layers are fitted by the same launches: the grid is split
+// the hardware favours them in.  A selection group of S weights (the weights
+// that share a table choice) is held by S/8 adjacent lanes; the scale group
+// (g >= S weights) only decides which reciprocal scale a lane reads.  Up to eight layers are fitted by the same launches: the grid is split
 // among them in proportion to their sizes and a block first looks up the layer
 // it belongs to.
 //
@@ -69,7 +70,7 @@ struct LayerArgs {
 };
 struct BatchArgs {
   int n;
-  int pad;
+  int gshift;  // log2 of the scale group size
   LayerArgs layer[kMaxFusedLayers];
 };
 
@@ -122,6 +123,7 @@ __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) 
 
 // pass: index of this pass (selects the accumulator and table buffers);
 // prev_trace: where the objective found in the previous pass's sums goes (-1: nowhere);
+// LANES: lanes per selection group (S / 8);
 // ASSIGN: assignment pass (true) or refinement pass with the stored choice (false).
 template <int LANES, bool ASSIGN>
 __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs batch, const int pass,
@@ -167,9 +169,10 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   const int col = strip * kStripCols + lane * 8;
   const bool has_strip = strip < strips;
   const bool active = has_strip && col < K;
-  const int G = K / (8 * LANES);
+  const int G = K / (8 * LANES);       // selection groups per row
+  const int Gs = K >> batch.gshift;    // scale groups per row
   const uint16_t* wbase = W + (active ? col : 0);
-  const float* rbase = rinv + (active ? col / (8 * LANES) : 0);
+  const float* rbase = rinv + (active ? col >> batch.gshift : 0);
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
   if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
   uint8_t* sbase = sigma_arr ? sigma_arr + (active ? col / (8 * LANES) : 0) : nullptr;
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   uint32_t s_next = 0;  // the stored choice of the next row's group (refinement passes)
   if (active && row < block_r1) {
     v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)row * ldw);
-    r_next = rbase[(int64_t)row * G];
+    r_next = rbase[(int64_t)row * Gs];
     if (!ASSIGN) s_next = sbase[(int64_t)row * G];
   }
   float Iv[8];
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
     next = __builtin_amdgcn_readfirstlane(next);
     if (active && next < block_r1) {
       v_next = *reinterpret_cast<const uint4*>(wbase + (int64_t)next * ldw);
-      r_next = rbase[(int64_t)next * G];
+      r_next = rbase[(int64_t)next * Gs];
       if (!ASSIGN) s_next = sbase[(int64_t)next * G];
     }
     row = next;
@@ -364,9 +367,9 @@ hipError_t launch_passes(const BatchArgs& batch, int blocks, int n_outer, int n_
 
 }  // namespace
 
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_budget) {
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cu_budget) {
   FitPlan p;
-  p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size;
+  p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size; p.sel_size = sel_size;
   p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
   const int64_t rows = N > 0 ? N : 1;
   // One block of 16 wavefronts per compute unit.  Among 1, 2, 4, 8, 16 strips per
@@ -401,17 +404,18 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int cu_
   p.off_rinv = align(sizeof(FitState));
   const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
   p.off_sigma = p.off_rinv + align(groups * sizeof(float));
-  p.bytes = p.off_sigma + align(groups);
+  p.bytes = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
   return p;
 }
 
-hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt, const Grid32& grid,
-                            int n_outer, int n_inner, hipStream_t stream) {
+hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel_size, int fmt,
+                            const Grid32& grid, int n_outer, int n_inner, hipStream_t stream) {
   const int iterations = n_outer;
   if (n <= 0) return hipSuccess;
   // every layer gets its state initialised and its outputs written; only layers
   // that hold weights take part in the iterations
   BatchArgs all = {}, work = {};
+  for (int g = group_size; g > 1; g >>= 1) ++work.gshift;
   double total = 0.0;
   for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
   const int cus = compute_units();
@@ -421,7 +425,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
     const double share = total > 0.0 ? (double)t.N * (double)t.K / total : 0.0;
     int budget = (int)(share * cus);
     if (budget < 1) budget = 1;
-    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, n == 1 ? 0 : budget);
+    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, n == 1 ? 0 : budget);
     char* base = static_cast<char*>(t.ws);
     LayerArgs a = {};
     a.W = static_cast<const uint16_t*>(t.W);
@@ -456,7 +460,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int fmt
       e = launch_group_rinv(a.W, a.N, a.K, a.ldw, group_size, fmt, const_cast<float*>(a.rinv), stream);
       if (e != hipSuccess) return e;
     }
-    switch (group_size / 8) {
+    switch (sel_size / 8) {
       case 2: e = launch_passes<2>(work, blocks, n_outer, n_inner, stream); break;
       case 4: e = launch_passes<4>(work, blocks, n_outer, n_inner, stream); break;
       case 8: e = launch_passes<8>(work, blocks, n_outer, n_inner, stream); break;

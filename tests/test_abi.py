@@ -97,16 +97,29 @@ def test_other_entry_points_validate():
     assert L.aaac_dequant(FAKE, FAKE, FAKE, 8, 64, 16, 0, FAKE, 63, None) == E_SHAPE
     assert L.aaac_dequant(FAKE, FAKE, FAKE, 8, 64, 16, 3, FAKE, 64, None) == E_ARG
     assert L.aaac_fit_batch(None, 1, 16, 0, FAKE, 1, FAKE, 1 << 20, None) == E_NULL
-    assert L.aaac_fit_nested(None, 1, 16, 0, FAKE, 1, 1, FAKE, 1 << 20, None) == E_NULL
+    assert L.aaac_fit_nested(None, 1, 16, 16, 0, FAKE, 1, 1, FAKE, 1 << 20, None) == E_NULL
     layer = A.binding.aaac_layer_t(0x10000, 8, 64, 64, 0x10000, None, 0x10000, None)
     arr = (A.binding.aaac_layer_t * 1)(layer)
     grid = np.concatenate([np.arange(16), np.arange(16)]).astype(np.float32)
     gp = grid.ctypes.data_as(ctypes.c_void_p)
-    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 1, 0, FAKE, 1 << 20, None) == E_ARG    # no inner step
-    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, -1, 2, FAKE, 1 << 20, None) == E_ARG
-    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 1 << 20, 1 << 20, FAKE, 1 << 20, None) == E_ARG  # pass count overflows
-    assert L.aaac_fit_nested(arr, 1, 16, 0, gp, 2, 2, FAKE, 16, None) == E_WS
-    assert L.aaac_fit_nested_workspace(arr, 1, 16, 0) == L.aaac_fit_batch_workspace(arr, 1, 16, 0) > 0
+    assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, 1, 0, FAKE, 1 << 20, None) == E_ARG    # no inner step
+    assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, -1, 2, FAKE, 1 << 20, None) == E_ARG
+    assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, 1 << 20, 1 << 20, FAKE, 1 << 20, None) == E_ARG  # pass count overflows
+    assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, 2, 2, FAKE, 16, None) == E_WS
+    assert L.aaac_fit_nested_workspace(arr, 1, 16, 16, 0) == L.aaac_fit_batch_workspace(arr, 1, 16, 0) > 0
+    # selection groups: a size that divides the scale group, 16..128
+    assert L.aaac_fit_nested(arr, 1, 16, 32, 0, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE  # larger than the scale group
+    assert L.aaac_fit_nested(arr, 1, 64, 8, 1, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE
+    assert L.aaac_fit_nested(arr, 1, 64, 24, 1, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE
+    assert L.aaac_fit_nested_workspace(arr, 1, 64, 24, 1) == 0
+    assert L.aaac_fit_nested_workspace(arr, 1, 64, 16, 1) >= L.aaac_fit_nested_workspace(arr, 1, 64, 64, 1) > 0
+    assert L.aaac_encode_sel(FAKE, 8, 128, 128, 64, 16, 1, FAKE, FAKE, FAKE, FAKE, None, 1, None) == E_NULL
+    assert L.aaac_encode_sel(FAKE, 8, 128, 128, 64, 16, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 0, None) == E_SHAPE  # stride < 1
+    assert L.aaac_encode_sel(FAKE, 8, 128, 128, 64, 128, 1, FAKE, FAKE, FAKE, FAKE, FAKE, 1, None) == E_SHAPE
+    assert L.aaac_encode_sel(FAKE, 8, 128, 128, 64, 16, 5, FAKE, FAKE, FAKE, FAKE, FAKE, 1, None) == E_ARG
+    assert L.aaac_dequant_sel(FAKE, FAKE, None, 1, FAKE, 8, 128, 64, 16, 1, FAKE, 128, None) == E_NULL
+    assert L.aaac_dequant_sel(FAKE, FAKE, FAKE, 0, FAKE, 8, 128, 64, 16, 1, FAKE, 128, None) == E_SHAPE
+    assert L.aaac_dequant_sel(FAKE, FAKE, FAKE, 1, FAKE, 8, 128, 64, 48, 1, FAKE, 128, None) == E_SHAPE
 
 
 def test_binding_raises_with_message():

@@ -342,10 +342,10 @@ def test_batch_of_more_layers_than_one_launch_group_and_an_empty_layer():
         assert np.allclose(host(ob)[:iters], ref["objective"], rtol=1e-9)
 
 
-def nested_on_gpu(Ws, Is, g, fmt, grid, n_outer, n_inner):
+def nested_on_gpu(Ws, Is, g, fmt, grid, n_outer, n_inner, S=None):
     layers, outs = A.make_layers(Ws, Is, n_outer)
-    ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt), dtype=torch.uint8, device=DEV)
-    A.aaac_fit_nested(layers, g, fmt, grid, n_outer, n_inner, ws)
+    ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt, sel_size=S), dtype=torch.uint8, device=DEV)
+    A.aaac_fit_nested(layers, g, fmt, grid, n_outer, n_inner, ws, sel_size=S)
     torch.cuda.synchronize()
     return outs
 
@@ -414,6 +414,82 @@ def test_nested_loops_cfg1_full_size():
     assert (u16(tb) == ref["tables_bf16"]).all()
     assert tables_close(host(tf), ref["tables_f32"])
     assert np.allclose(host(ob)[:3], ref["objective"], rtol=1e-9)
+
+
+# ------------------------------------------ selection groups smaller than scale groups
+
+def check_sel_layer(Wt, I, g, S, fmt, n_outer, n_inner, grid=None, pad_stride=0):
+    """Fit, encode and dequantise with S < g on the GPU and compare everything with the oracle."""
+    grid = inputs.format_grid(fmt) if grid is None else grid
+    Ih = host(I)
+    ref = oracle.fit_sel(inputs.bits(Wt), g, S, fmt, Ih, grid, n_outer, n_inner)
+    (tf, tb, ob), = nested_on_gpu([Wt], [I], g, fmt, grid, n_outer, n_inner, S=S)
+    assert (u16(tb) == ref["tables_bf16"]).all()
+    assert tables_close(host(tf), ref["tables_f32"])
+    if n_outer:
+        assert np.allclose(host(ob)[:n_outer], ref["objective"], rtol=1e-9)
+    N, K = Wt.shape
+    stride = A.sel_stride(K, S) + pad_stride
+    bits = torch.full((N, stride), 0xFF, dtype=torch.uint8, device=DEV) if S < g else None
+    codes, scales, bits = A.aaac_encode_sel(Wt, g, S, fmt, I, tb, sel_bits=bits)
+    What = A.aaac_dequant_sel(codes, scales, bits, tb, g, S, fmt)
+    torch.cuda.synchronize()
+    rc, rs, rb = oracle.encode_sel(inputs.bits(Wt), g, S, fmt, Ih, ref["tables_bf16"])
+    assert (host(codes) == rc).all()
+    assert (host(scales).view(rs.dtype) == rs).all()
+    if S < g:
+        used = A.sel_stride(K, S)
+        assert (host(bits)[:, :used] == rb).all()
+        assert (host(bits)[:, used:] == 0xFF).all()          # bytes past the row's bits are not touched
+        assert (host(scales).view(rs.dtype) >> (7 if fmt == A.NVFP4 else 15) == 0).all()
+    assert (u16(What) == oracle.dequant_sel(rc, rs, rb, ref["tables_bf16"], g, S, fmt)).all()
+    return ref
+
+
+@pytest.mark.parametrize("N,K,g,S,fmt,n_outer,n_inner,pad", [
+    (128, 4096, 128, 16, 1, 3, 4, 0),    # the paper's INT4 setting with S = 16
+    (37, 1152, 128, 16, 1, 2, 1, 3),     # ragged: 2.25 strips, 9 selection bytes per row, padded stride
+    (64, 640, 64, 32, 1, 2, 2, 0),
+    (50, 1536, 128, 64, 1, 2, 2, 1),
+    (96, 1056, 32, 16, 0, 2, 2, 0),      # 66 selection groups: the last byte of a row holds two bits
+    (33, 512, 128, 32, 0, 1, 3, 0),
+    (40, 2048, 64, 64, 1, 2, 2, 0),      # S == g through the same entry points: sign-bit path
+])
+def test_selection_groups_smaller_than_scale_groups(N, K, g, S, fmt, n_outer, n_inner, pad):
+    say(f"[sel] N={N} K={K} g={g} S={S} fmt={fmt} outer={n_outer} inner={n_inner}")
+    Wt = inputs.make_weight(N, K, "gauss_outlier", 500 + N + K, DEV)
+    I = torch.from_numpy(oracle.act_stats(inputs.bits(
+        inputs.make_activations(64, K, ("gauss", 0.01, "u10_50"), 510 + K, DEV)))).to(DEV)
+    check_sel_layer(Wt, I, g, S, fmt, n_outer, n_inner, pad_stride=pad)
+
+
+def test_selection_groups_worked_vector():
+    case = GOLD["sel_cases"][0]
+    g, S, fmt = case["g"], case["S"], A.INT4
+    Wt = torch.tensor(case["W"], dtype=torch.float32, device=DEV).to(torch.bfloat16)[None, :]
+    tb = torch.tensor(case["T0"] + case["T1"], dtype=torch.float32, device=DEV).to(torch.bfloat16).view(torch.int16)
+    I = (torch.arange(Wt.shape[1], device=DEV) % 5 + 1).float()
+    codes, scales, bits = A.aaac_encode_sel(Wt, g, S, fmt, I, tb)
+    What = A.aaac_dequant_sel(codes, scales, bits, tb, g, S, fmt)
+    torch.cuda.synchronize()
+    c = host(codes)[0]
+    assert np.stack([c & 15, c >> 4], axis=1).reshape(-1).tolist() == case["codes"]
+    assert host(scales).view(np.uint16).tolist() == [[case["scale"]]]
+    assert host(bits).tolist() == [case["sel_bits"]]
+    assert (What == Wt).all()
+
+
+def test_selection_groups_cfg1_shape_full_size():
+    """4096x4096, INT4 g=128 with one choice per 16 weights (+1/16 bit per weight)."""
+    cfg = inputs.CONFIGS[1]
+    l = cfg["layers"][0]
+    Wt = inputs.layer_weights(l, DEV)
+    I = torch.rand(l["K"], device=DEV) * 100 + 1
+    t0 = time.time()
+    ref = check_sel_layer(Wt, I, cfg["g"], 16, cfg["fmt"], 2, 3)
+    coarse = oracle.fit_sel(inputs.bits(Wt), cfg["g"], cfg["g"], cfg["fmt"], host(I), inputs.format_grid(cfg["fmt"]), 2, 3)
+    say(f"[sel] cfg1 S=16 {time.time() - t0:.1f}s, objective {ref['objective'][-1]:.4e} vs S=128 {coarse['objective'][-1]:.4e}")
+    assert ref["objective"][-1] < coarse["objective"][-1]
 
 
 # ------------------------------------------ benchmark settings, full size
