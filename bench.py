@@ -52,6 +52,9 @@ def main():
                     help="k-means steps per assignment step (Alg. 1's inner loop); above 1 the fit goes through "
                          "aaac_fit_nested with --n-outer assignment steps")
     ap.add_argument("--n-outer", type=int, default=None, help="assignment steps when --n-inner > 1 (default 3)")
+    ap.add_argument("--sel-size", type=int, default=None,
+                    help="weights per table choice when smaller than the scale group (selection bits stored "
+                         "separately); the fit then goes through aaac_fit_nested")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -76,8 +79,9 @@ def main():
     warmup = args.warmup if args.warmup is not None else (1 if big else 3)
     g, fmt, iters = cfg["g"], cfg["fmt"], cfg["iters"]
     grid = inputs.format_grid(fmt)
-    nested = args.n_inner > 1
-    n_outer = (args.n_outer if args.n_outer is not None else 3) if nested else iters
+    S = args.sel_size if args.sel_size is not None else g
+    nested = args.n_inner > 1 or S != g
+    n_outer = args.n_outer if args.n_outer is not None else (3 if args.n_inner > 1 else iters)
     n_inner = args.n_inner
     iters = n_outer  # length of the objective trace
     passes = n_outer * n_inner  # passes over the weights per fit
@@ -98,6 +102,7 @@ def main():
             codes=torch.empty((N, K // 2), dtype=torch.uint8, device=dev),
             scales=torch.empty((N, K // g), dtype=torch.uint8 if fmt == A.NVFP4 else torch.int16, device=dev),
             What=torch.empty((N, K), dtype=torch.bfloat16, device=dev),
+            bits=torch.empty((N, A.sel_stride(K, S)), dtype=torch.uint8, device=dev) if S < g else None,
             ws=torch.empty(A.aaac_fit_workspace(N, K, g, fmt), dtype=torch.uint8, device=dev)))
     if batch:
         import ctypes
@@ -105,7 +110,7 @@ def main():
         for i, L in enumerate(layers):
             arr[i] = A.binding.aaac_layer_t(L["W"].data_ptr(), L["N"], L["K"], L["W"].stride(0), Is[L["x"]].data_ptr(),
                                             L["tf"].data_ptr(), L["tb"].data_ptr(), L["obj"].data_ptr())
-        ws_batch = torch.empty(A.aaac_fit_nested_workspace(arr, g, fmt), dtype=torch.uint8, device=dev)
+        ws_batch = torch.empty(A.aaac_fit_nested_workspace(arr, g, fmt, sel_size=S), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
     n_w = sum(L["N"] * L["K"] for L in layers)
 
@@ -118,7 +123,7 @@ def main():
             A.aaac_act_stats(X, Is[k], ws_stats[k], stream)
         mark(1)
         if nested:
-            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, n_inner, ws_batch, stream)
+            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, n_inner, ws_batch, stream, sel_size=S)
         elif batch:
             A.aaac_fit_batch(arr, g, fmt, grid, iters, ws_batch, stream)
         else:
@@ -126,10 +131,16 @@ def main():
                 A.aaac_fit(L["W"], g, fmt, Is[L["x"]], grid, iters, L["tf"], L["tb"], L["obj"], L["ws"], stream)
         mark(2)
         for L in layers:
-            A.aaac_encode(L["W"], g, fmt, Is[L["x"]], L["tb"], L["codes"], L["scales"], stream)
+            if S < g:
+                A.aaac_encode_sel(L["W"], g, S, fmt, Is[L["x"]], L["tb"], L["codes"], L["scales"], L["bits"], stream)
+            else:
+                A.aaac_encode(L["W"], g, fmt, Is[L["x"]], L["tb"], L["codes"], L["scales"], stream)
         mark(3)
         for L in layers:
-            A.aaac_dequant(L["codes"], L["scales"], L["tb"], g, fmt, L["What"], stream)
+            if S < g:
+                A.aaac_dequant_sel(L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt, L["What"], stream)
+            else:
+                A.aaac_dequant(L["codes"], L["scales"], L["tb"], g, fmt, L["What"], stream)
         mark(4)
 
     for _ in range(warmup):
@@ -152,14 +163,14 @@ def main():
     value = n_w * passes / (ms_per_step * 1e-3)
 
     refine = None
-    if nested:
+    if n_inner > 1:
         # refinement pass alone: the same fit with one inner step costs n_outer assignment passes
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = max(steps, 3)
-        A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream)
+        A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream, sel_size=S)
         e0.record(stream)
         for _ in range(reps):
-            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream)
+            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream, sel_size=S)
         e1.record(stream)
         torch.cuda.synchronize()
         assign_ms = e0.elapsed_time(e1) / reps
@@ -201,7 +212,7 @@ def main():
         "config": {"workload": cfg["name"], "layers": [f'{L["name"]} {L["N"]}x{L["K"]} bf16' for L in layers],
                    "tokens": int(next(iter(Xs.values())).shape[0]), "group_size": g,
                    "format": "nvfp4" if fmt == A.NVFP4 else "int4", "iterations": iters,
-                   "n_inner": n_inner, "passes_per_fit": passes},
+                   "n_inner": n_inner, "passes_per_fit": passes, "sel_size": S},
         "layer_fit_ms": fit_ms + enc_ms,
         "stage_ms": {"act_stats": stats_ms, "fit": fit_ms, "encode": enc_ms, "dequant": deq_ms},
         "act_stats_GBs": x_bytes / (stats_ms * 1e-3) / 1e9,
@@ -226,7 +237,7 @@ def main():
         Ih = Is[L["x"]].cpu().numpy()
         t1 = time.perf_counter()
         if nested:
-            oracle.fit_nested(Wb, g, fmt, Ih, grid, n_outer, n_inner)
+            oracle.fit_sel(Wb, g, S, fmt, Ih, grid, n_outer, n_inner)
         else:
             oracle.fit(Wb, g, fmt, Ih, grid, iters)
         dt = time.perf_counter() - t1
