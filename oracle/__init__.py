@@ -68,6 +68,8 @@ def lib():
         L.oracle_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64]
         L.oracle_dequant_sel.restype = _INT
         L.oracle_dequant_sel.argtypes = [_P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64]
+        L.oracle_quantile_init.restype = _INT
+        L.oracle_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P]
         L.oracle_encode.restype = _INT
         L.oracle_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P]
         L.oracle_dequant.restype = _INT
@@ -282,3 +284,12 @@ def dequant_sel(codes, scales, sel_bits, tables_bf16, g, S, fmt):
     _check(lib().oracle_dequant_sel(_ptr(codes), _ptr(scales), _ptr(bits), 0 if bits is None else bits.shape[1],
                                     _ptr(tb), N, K, g, S, fmt, _ptr(out), K), "dequant_sel")
     return out
+
+
+def quantile_init(W_bits, g, fmt):
+    """Initial tables from quantiles of the normalised weights -> float32 [32] (T0 then T1)."""
+    W = _c(W_bits, np.uint16)
+    N, K = W.shape
+    grid = np.empty(32, np.float32)
+    _check(lib().oracle_quantile_init(_ptr(W), N, K, K, g, fmt, _ptr(grid)), "quantile_init")
+    return grid

@@ -557,4 +557,41 @@ int oracle_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* 
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Quantile initialisation (Eq. "init_t0", Eq. "init_t1"; Alg. 1 steps 4-5) with
+// M = 16 entries per table: T0[i] = Quantile_{i/15}, T1[i] = Quantile_{d + (1-d) i/15},
+// d = 1/30, of all N*K normalised weights of the layer.
+//
+// Quantile convention (the paper names none): linear interpolation between order
+// statistics, position q * (n - 1) counted from 0 in the ascending sequence
+// x_(0) <= ... <= x_(n-1).  The quantile levels are rationals, q = num/den with
+// (num, den) = (i, 15) for T0 and (15 + 29 i, 450) for T1, so the position is
+// split exactly in integers: lo = num*(n-1) div den, rem = num*(n-1) mod den, and
+//   value = fl32( x_(lo) + (rem/den) * (x_(lo+1) - x_(lo)) )  evaluated in fp64
+// (x_(lo+1) is not read when rem == 0).
+int oracle_quantile_init(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int fmt,
+                         float* grid32) {
+  if (!valid_shape(N, K, ldw, g) || N == 0 || K == 0) return -1;
+  std::vector<float> x(static_cast<size_t>(N) * K);
+  int rc = oracle_normalise(W, N, K, ldw, g, fmt, nullptr, nullptr, x.data());
+  if (rc) return rc;
+  std::sort(x.begin(), x.end());
+  const unsigned __int128 last = static_cast<unsigned __int128>(x.size() - 1);
+  for (int t = 0; t < 2; ++t)
+    for (int i = 0; i < 16; ++i) {
+      unsigned __int128 num = (t == 0) ? i : 15 + 29 * i;
+      unsigned __int128 den = (t == 0) ? 15 : 450;
+      unsigned __int128 pos = num * last;
+      size_t lo = static_cast<size_t>(pos / den);
+      double rem = static_cast<double>(static_cast<uint64_t>(pos % den));
+      double v = static_cast<double>(x[lo]);
+      if (rem != 0.0) {
+        double frac = rem / static_cast<double>(static_cast<uint64_t>(den));
+        v = v + frac * (static_cast<double>(x[lo + 1]) - v);
+      }
+      grid32[16 * t + i] = static_cast<float>(v);
+    }
+  return 0;
+}
+
 }  // extern "C"
