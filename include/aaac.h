@@ -118,13 +118,32 @@ int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaa
  * centroids (empty cell: keep), and the tables are sorted after each step.
  * n_inner = 1 with sel_size = group_size is aaac_fit_batch with iterations = n_outer.
  * objective_trace of a layer holds n_outer values (the objective seen by each
- * assignment step).  n_outer >= 0, n_inner >= 1.  Errors as aaac_fit; a sel_size that
- * is not allowed is AAAC_ERR_SHAPE. */
+ * assignment step).  n_outer >= 0, n_inner >= 1.
+ * init_grid (HOST, 32 floats) as in aaac_fit, or NULL: the tables then start from the
+ * quantiles of each layer's normalised weights, as Alg. 1 steps 4-5 state (see
+ * aaac_quantile_init); a layer without weights is then AAAC_ERR_SHAPE.
+ * Errors as aaac_fit; a sel_size that is not allowed is AAAC_ERR_SHAPE. */
 size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int group_size,
                                  int sel_size, aaac_format_t fmt);
 int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, int sel_size,
                     aaac_format_t fmt, const float* init_grid, int n_outer, int n_inner, void* ws,
                     size_t ws_bytes, void* hip_stream);
+
+/* ---- Quantile initialisation of the two tables (paper Eq. "init_t0", Eq. "init_t1";
+ * Alg. 1 steps 4-5), 16 entries each:
+ *   T0[i] = Quantile_{i/15},  T1[i] = Quantile_{1/30 + (29/30) i/15},  i = 0..15,
+ * of all N*K normalised weights w~ of the layer.  The quantile of level q = num/den
+ * is taken by linear interpolation between order statistics x_(0) <= ... <= x_(n-1):
+ * with lo = num*(n-1) div den and rem = num*(n-1) mod den (exact integers),
+ * value = fl32( x_(lo) + (rem/den) * (x_(lo+1) - x_(lo)) ) evaluated in fp64; a zero is
+ * stored as +0.  The order statistics are exact (radix select, no sampling).
+ *   grid   dev fp32 [32], overwritten: T0[0..15] then T1[0..15], each ascending
+ *   ws     dev scratch of aaac_quantile_init_workspace(...) bytes, 256-byte aligned
+ * N = 0 or K = 0 is AAAC_ERR_SHAPE (no weights to take quantiles of); other errors as
+ * aaac_fit. */
+size_t aaac_quantile_init_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt);
+int aaac_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size,
+                       aaac_format_t fmt, float* grid, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* ---- Final encode (paper Alg. 1, last four steps; Eq. "aaac_code").  With the
  * bf16 tables (each non-decreasing), recompute sigma per group, write each

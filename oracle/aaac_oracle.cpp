@@ -568,7 +568,9 @@ int oracle_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* 
 // (num, den) = (i, 15) for T0 and (15 + 29 i, 450) for T1, so the position is
 // split exactly in integers: lo = num*(n-1) div den, rem = num*(n-1) mod den, and
 //   value = fl32( x_(lo) + (rem/den) * (x_(lo+1) - x_(lo)) )  evaluated in fp64
-// (x_(lo+1) is not read when rem == 0).
+// (x_(lo+1) is not read when rem == 0).  A zero result is stored as +0 whatever
+// the sign of the zero weight it came from (the order of -0 and +0 in the sorted
+// sequence is not defined by their values).
 int oracle_quantile_init(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int g, int fmt,
                          float* grid32) {
   if (!valid_shape(N, K, ldw, g) || N == 0 || K == 0) return -1;
@@ -589,7 +591,7 @@ int oracle_quantile_init(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, i
         double frac = rem / static_cast<double>(static_cast<uint64_t>(den));
         v = v + frac * (static_cast<double>(x[lo + 1]) - v);
       }
-      grid32[16 * t + i] = static_cast<float>(v);
+      grid32[16 * t + i] = static_cast<float>(v) + 0.0f;  // -0 becomes +0
     }
   return 0;
 }

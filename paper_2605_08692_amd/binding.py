@@ -62,6 +62,10 @@ def library():
         L.aaac_fit_nested_workspace.argtypes = [_P, _INT, _INT, _INT, _INT]
         L.aaac_fit_nested.restype = _INT
         L.aaac_fit_nested.argtypes = [_P, _INT, _INT, _INT, _INT, _P, _INT, _INT, _P, _SZ, _P]
+        L.aaac_quantile_init_workspace.restype = _SZ
+        L.aaac_quantile_init_workspace.argtypes = [_I64, _I64, _INT, _INT]
+        L.aaac_quantile_init.restype = _INT
+        L.aaac_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _SZ, _P]
         L.aaac_encode_sel.restype = _INT
         L.aaac_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64, _P]
         L.aaac_dequant_sel.restype = _INT
@@ -187,11 +191,12 @@ def aaac_fit_nested_workspace(layers, group_size, fmt, sel_size=None):
 
 def aaac_fit_nested(layers, group_size, fmt, init_grid, n_outer, n_inner, ws, stream=None, sel_size=None):
     """Both loops of the learning algorithm, one table choice per sel_size weights (default: per
-    scale group); layers: array from make_layers (objective: n_outer values)."""
-    g = _grid(init_grid)
+    scale group); layers: array from make_layers (objective: n_outer values).  init_grid None:
+    the tables start from the quantiles of each layer's normalised weights."""
+    g = None if init_grid is None else _grid(init_grid)
     _check(library().aaac_fit_nested(layers, len(layers), group_size, sel_size or group_size, fmt,
-                                     ctypes.c_void_p(g.data_ptr()), n_outer, n_inner, _dp(ws), ws.numel(),
-                                     _stream(stream)), "aaac_fit_nested")
+                                     None if g is None else ctypes.c_void_p(g.data_ptr()), n_outer, n_inner,
+                                     _dp(ws), ws.numel(), _stream(stream)), "aaac_fit_nested")
 
 
 def aaac_encode(W, group_size, fmt, importance, tables_bf16, codes=None, scales=None, stream=None):
@@ -254,3 +259,21 @@ def aaac_dequant_sel(codes, scales, sel_bits, tables_bf16, group_size, sel_size,
                                       group_size, sel_size, fmt, _dp(W_hat), ldo, _stream(stream)),
            "aaac_dequant_sel")
     return W_hat
+
+
+def aaac_quantile_init_workspace(N, K, group_size, fmt):
+    return library().aaac_quantile_init_workspace(N, K, group_size, fmt)
+
+
+def aaac_quantile_init(W, group_size, fmt, grid=None, ws=None, stream=None):
+    """Initial tables from quantiles of the normalised weights -> fp32 [32] on W's device."""
+    assert W.dtype == torch.bfloat16 and W.dim() == 2 and W.stride(1) == 1
+    N, K = W.shape
+    if grid is None:
+        grid = torch.empty(32, dtype=torch.float32, device=W.device)
+    if ws is None:
+        ws = _workspace(aaac_quantile_init_workspace(N, K, group_size, fmt), W.device)
+    ldw = W.stride(0) if N > 1 else max(W.stride(0), K)
+    _check(library().aaac_quantile_init(_dp(W), N, K, ldw, group_size, fmt, _dp(grid), _dp(ws), ws.numel(),
+                                        _stream(stream)), "aaac_quantile_init")
+    return grid

@@ -94,10 +94,32 @@ size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fm
   return aaac::make_fit_plan(N, K, K, group_size, group_size).bytes;
 }
 
+size_t aaac_quantile_init_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt) {
+  return aaac_fit_workspace(N, K, group_size, fmt);
+}
+
+int aaac_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
+                       float* grid, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (W == nullptr || grid == nullptr) return AAAC_ERR_NULL;
+  int rc = check_matrix(W, N, K, ldw, group_size);
+  if (rc) return rc;
+  if (N == 0 || K == 0) return AAAC_ERR_SHAPE;
+  if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
+  const aaac::FitPlan p = aaac::make_fit_plan(N, K, ldw, group_size, group_size);
+  rc = check_ws(ws, ws_bytes, p.bytes);
+  if (rc) return rc;
+  char* base = static_cast<char*>(ws);
+  float* rinv = reinterpret_cast<float*>(base + p.off_rinv);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (aaac::launch_group_rinv(W, N, K, ldw, group_size, fmt, rinv, stream) != hipSuccess) return AAAC_ERR_HIP;
+  return from_hip(aaac::launch_quantile_init(W, N, K, ldw, group_size, rinv, base + p.off_quant, grid, stream));
+}
+
 int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
              const float* importance, const float* init_grid, int iterations, float* tables_f32,
              uint16_t* tables_bf16, double* objective_trace, void* ws, size_t ws_bytes,
              void* hip_stream) {
+  if (init_grid == nullptr) return AAAC_ERR_NULL;
   aaac_layer_t layer = {W, N, K, ldw, importance, tables_f32, tables_bf16, objective_trace};
   return aaac_fit_batch(&layer, 1, group_size, fmt, init_grid, iterations, ws, ws_bytes, hip_stream);
 }
@@ -110,6 +132,7 @@ size_t aaac_fit_batch_workspace(const aaac_layer_t* layers, int n_layers, int gr
 int aaac_fit_batch(const aaac_layer_t* layers, int n_layers, int group_size, aaac_format_t fmt,
                    const float* init_grid, int iterations, void* ws, size_t ws_bytes,
                    void* hip_stream) {
+  if (init_grid == nullptr) return AAAC_ERR_NULL;
   return aaac_fit_nested(layers, n_layers, group_size, group_size, fmt, init_grid, iterations, 1, ws, ws_bytes,
                          hip_stream);
 }
@@ -130,7 +153,7 @@ size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int g
 int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, int sel_size,
                     aaac_format_t fmt, const float* init_grid, int n_outer, int n_inner, void* ws,
                     size_t ws_bytes, void* hip_stream) {
-  if (layers == nullptr || init_grid == nullptr) return AAAC_ERR_NULL;
+  if (layers == nullptr) return AAAC_ERR_NULL;
   if (n_layers < 0) return AAAC_ERR_SHAPE;
   if (!valid_fmt(fmt) || n_outer < 0 || n_inner < 1) return AAAC_ERR_ARG;
   if ((int64_t)n_outer * n_inner > (int64_t)1 << 30) return AAAC_ERR_ARG;
@@ -139,13 +162,20 @@ int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, in
     int rc = check_layer(layers[i], group_size);
     if (rc) return rc;
   }
-  int rc = check_grid(init_grid);
-  if (rc) return rc;
+  int rc = AAAC_OK;
+  if (init_grid != nullptr) {
+    rc = check_grid(init_grid);
+    if (rc) return rc;
+  } else {  // quantile initialisation needs weights to take quantiles of
+    for (int i = 0; i < n_layers; ++i)
+      if (layers[i].N == 0 || layers[i].K == 0) return AAAC_ERR_SHAPE;
+  }
   rc = check_ws(ws, ws_bytes, aaac_fit_nested_workspace(layers, n_layers, group_size, sel_size, fmt));
   if (rc) return rc;
 
-  aaac::Grid32 grid;
-  for (int i = 0; i < 32; ++i) grid.t[i] = init_grid[i];
+  aaac::Grid32 grid = {};
+  if (init_grid != nullptr)
+    for (int i = 0; i < 32; ++i) grid.t[i] = init_grid[i];
   char* base = static_cast<char*>(ws);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   // the layers are fitted in groups whose passes share one launch each
@@ -157,7 +187,8 @@ int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, in
       tasks[n] = {l.W, l.N, l.K, l.ldw, l.importance, l.tables_f32, l.tables_bf16, l.objective_trace, base};
       base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size, sel_size).bytes);
     }
-    if (aaac::launch_fit_group(tasks, n, group_size, sel_size, fmt, grid, n_outer, n_inner, stream) != hipSuccess)
+    if (aaac::launch_fit_group(tasks, n, group_size, sel_size, fmt, init_grid ? &grid : nullptr, n_outer, n_inner,
+                               stream) != hipSuccess)
       return AAAC_ERR_HIP;
   }
   return AAAC_OK;

@@ -20,6 +20,34 @@ struct FitState {
   double acc[3][kAccCopies][kAccStride];  // sums of iteration t at [t % 3], spread over copies
 };
 
+// State of the quantile initialisation (radix select over the keys of the
+// normalised weights); lives in the layer's workspace.
+constexpr int kQuantSlots = 64;  // distinct key prefixes followed at once = wanted ranks at most
+struct QuantState {
+  unsigned long long hist1[4096];              // pass 1: counts per top 12 key bits
+  unsigned long long hist[kQuantSlots][256];   // passes 2-4: counts per slot and next key bits
+  uint8_t map1[4096];                          // top 12 bits -> slot of pass 2 (0xFF: not followed)
+  uint8_t map2[kQuantSlots][256];              // slot of pass 2, next 8 bits -> slot of pass 3
+  uint8_t map3[kQuantSlots][256];              // slot of pass 3, next 8 bits -> slot of pass 4
+  unsigned long long rank[kQuantSlots];        // rank of each target among the keys that share its prefix
+  uint32_t prefix[kQuantSlots];                // key bits found so far
+  uint8_t slot[kQuantSlots];
+  float grid[32];                              // the resulting tables when they feed a fit directly
+};
+struct QuantLevel {   // one quantile: value = x[lo] + rem/den * (x[hi] - x[lo]), lo/hi index the target list
+  uint32_t rem, den;
+  uint8_t lo, hi;
+};
+struct QuantTargets {  // passed to kernels by value
+  int count;                                   // wanted order statistics, <= 64
+  unsigned long long rank[kQuantSlots];        // ascending, distinct, counted from 0
+  QuantLevel level[32];                        // T0[0..15] then T1[0..15]
+};
+QuantTargets make_quant_targets(int64_t N, int64_t K);
+// rinv: the reciprocal scales of the layer (launch_group_rinv) must be enqueued before.
+hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size,
+                                const float* rinv, void* quant_state, float* grid_out, hipStream_t stream);
+
 // How a layer is cut into blocks for the Lloyd iteration: a block owns a
 // rectangle of `strips_per_block` 512-column strips x `rows_per_block` rows.
 struct FitPlan {
@@ -32,7 +60,7 @@ struct FitPlan {
   int rows_per_block;
   int blocks;            // strip_groups * ceil(N / rows_per_block)
   // workspace layout (byte offsets)
-  size_t off_state, off_rinv, off_sigma, bytes;
+  size_t off_state, off_rinv, off_sigma, off_quant, bytes;
 };
 // cu_budget: compute units this layer may fill (0 = all of the device's).
 FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cu_budget = 0);
@@ -58,11 +86,12 @@ struct FitTask {
   void* ws;  // this layer's workspace (make_fit_plan(...).bytes)
 };
 constexpr int kMaxFusedLayers = 8;  // layers whose iterations share one launch
+// grid == nullptr: the initial tables are the quantiles of each layer's normalised weights.
 // Fits n <= kMaxFusedLayers layers together: every pass over the weights is one launch that
 // covers all of them.  n_outer assignment passes, each followed by n_inner - 1 passes that
 // only refine the tables with the choice frozen.
 hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel_size, int fmt,
-                            const Grid32& grid, int n_outer, int n_inner, hipStream_t stream);
+                            const Grid32* grid, int n_outer, int n_inner, hipStream_t stream);
 hipError_t launch_group_rinv(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, int fmt,
                              float* rinv, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);

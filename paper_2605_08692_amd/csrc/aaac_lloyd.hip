@@ -59,6 +59,7 @@ struct LayerArgs {
   const float* importance;
   FitState* state;
   uint8_t* sigma;         // table choice per group, written by assignment passes (may be null)
+  const float* grid_dev;  // initial tables in device memory (null: the grid passed by value)
   double* objective_trace;
   float* tables_f32;      // outputs of the final kernel
   uint16_t* tables_bf16;
@@ -296,7 +297,8 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
 __global__ void init_state_kernel(const BatchArgs batch, const Grid32 grid) {
   FitState* state = batch.layer[blockIdx.x].state;
   const int tid = threadIdx.x;
-  if (tid < 32) state->tables[0][tid] = grid.t[tid];
+  const float* dev = batch.layer[blockIdx.x].grid_dev;
+  if (tid < 32) state->tables[0][tid] = dev ? dev[tid] : grid.t[tid];
   for (int i = tid; i < 3 * kAccCopies * kAccStride; i += blockDim.x) (&state->acc[0][0][0])[i] = 0.0;
 }
 
@@ -404,17 +406,19 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel
   p.off_rinv = align(sizeof(FitState));
   const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
   p.off_sigma = p.off_rinv + align(groups * sizeof(float));
-  p.bytes = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
+  p.off_quant = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
+  p.bytes = p.off_quant + align(sizeof(QuantState));
   return p;
 }
 
 hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel_size, int fmt,
-                            const Grid32& grid, int n_outer, int n_inner, hipStream_t stream) {
+                            const Grid32* grid, int n_outer, int n_inner, hipStream_t stream) {
   const int iterations = n_outer;
   if (n <= 0) return hipSuccess;
   // every layer gets its state initialised and its outputs written; only layers
   // that hold weights take part in the iterations
   BatchArgs all = {}, work = {};
+  QuantState* quant[kMaxFusedLayers] = {};  // of the layers in `work`
   for (int g = group_size; g > 1; g >>= 1) ++work.gshift;
   double total = 0.0;
   for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
@@ -433,6 +437,8 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
     a.importance = t.importance;
     a.state = reinterpret_cast<FitState*>(base + p.off_state);
     a.sigma = n_inner > 1 ? reinterpret_cast<uint8_t*>(base + p.off_sigma) : nullptr;
+    QuantState* qs = reinterpret_cast<QuantState*>(base + p.off_quant);
+    a.grid_dev = grid ? nullptr : qs->grid;
     a.objective_trace = t.objective_trace;
     a.tables_f32 = t.tables_f32;
     a.tables_bf16 = t.tables_bf16;
@@ -447,19 +453,27 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
     if (t.N > 0 && t.K > 0) {
       a.block_begin = blocks;
       blocks += p.blocks;
+      quant[work.n] = qs;
       work.layer[work.n++] = a;
     }
   }
-  init_state_kernel<<<all.n, 256, 0, stream>>>(all, grid);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  int done = 0;
-  if (work.n > 0 && iterations > 0) {
+  hipError_t e = hipSuccess;
+  // reciprocal scales, then (without a caller's grid) the quantile tables, which need them
+  if (iterations > 0 || !grid)
     for (int i = 0; i < work.n; ++i) {
       const LayerArgs& a = work.layer[i];
       e = launch_group_rinv(a.W, a.N, a.K, a.ldw, group_size, fmt, const_cast<float*>(a.rinv), stream);
       if (e != hipSuccess) return e;
+      if (!grid) {
+        e = launch_quantile_init(a.W, a.N, a.K, a.ldw, group_size, a.rinv, quant[i], quant[i]->grid, stream);
+        if (e != hipSuccess) return e;
+      }
     }
+  init_state_kernel<<<all.n, 256, 0, stream>>>(all, grid ? *grid : Grid32{});
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  int done = 0;
+  if (work.n > 0 && iterations > 0) {
     switch (sel_size / 8) {
       case 2: e = launch_passes<2>(work, blocks, n_outer, n_inner, stream); break;
       case 4: e = launch_passes<4>(work, blocks, n_outer, n_inner, stream); break;

@@ -1,0 +1,300 @@
+// Quantile initialisation of the two tables (paper Eq. "init_t0", Eq. "init_t1";
+// Alg. 1 steps 4-5) for gfx950: T0[i] and T1[i] are quantiles of all N*K
+// normalised weights of a layer, linear interpolation between order statistics.
+//
+// The order statistics are found exactly, without sorting, by a radix select over
+// the order-preserving 32-bit key of w~ = w * (1/s): four passes over the weights
+// (12 + 8 + 8 + 4 key bits), each a histogram in LDS (merged into global memory
+// with 64-bit atomics), each followed by a one-block kernel that walks the
+// histogram for all wanted ranks at once.  At most 64 ranks are wanted (32
+// quantiles, two neighbouring order statistics each); after a pass, the ranks
+// that still share a key prefix share a "slot", and the next pass only counts
+// keys whose prefix has a slot, looked up through small tables in LDS.
+// Everything here is integer work except the final interpolation, which is a
+// fixed sequence of fp64 operations.
+#include "aaac_device.h"
+#include "aaac_internal.h"
+
+namespace aaac {
+
+namespace {
+
+constexpr int kQBlock = 1024;
+
+// float bits -> unsigned key with the same order as the float values (-0 < +0)
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t b = __float_as_uint(x);
+  return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+  return __uint_as_float(k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
+// Key bits consumed before pass P and the bits it looks at.
+template <int PASS> struct PassBits;
+template <> struct PassBits<1> { static constexpr int shift = 20, bins = 4096; };
+template <> struct PassBits<2> { static constexpr int shift = 12, bins = 256; };
+template <> struct PassBits<3> { static constexpr int shift = 4, bins = 256; };
+template <> struct PassBits<4> { static constexpr int shift = 0, bins = 16; };
+
+struct QuantLds {
+  uint32_t hist[kQuantSlots * 256];  // pass 1 uses the first 4096 counters
+  uint8_t map1[4096];
+  uint8_t map2[kQuantSlots][256];
+  uint8_t map3[kQuantSlots][256];
+};
+
+// One histogram pass.  The matrix is cut into 16-byte chunks (8 weights); block b
+// owns chunks [b * per_block, (b + 1) * per_block), a thread takes every 1024th.
+template <int PASS>
+__global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __restrict__ W,
+                                                             const float* __restrict__ rinv, int64_t N, int K,
+                                                             int64_t ldw, int gshift, int64_t per_block,
+                                                             QuantState* __restrict__ qs) {
+  __shared__ QuantLds sm;
+  constexpr int kCounters = PASS == 1 ? 4096 : kQuantSlots * PassBits<PASS>::bins;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kCounters; i += kQBlock) sm.hist[i] = 0u;
+  if (PASS >= 2)
+    for (int i = tid; i < 4096 / 4; i += kQBlock)
+      reinterpret_cast<uint32_t*>(sm.map1)[i] = reinterpret_cast<const uint32_t*>(qs->map1)[i];
+  if (PASS >= 3)
+    for (int i = tid; i < kQuantSlots * 256 / 4; i += kQBlock)
+      reinterpret_cast<uint32_t*>(&sm.map2[0][0])[i] = reinterpret_cast<const uint32_t*>(&qs->map2[0][0])[i];
+  if (PASS >= 4)
+    for (int i = tid; i < kQuantSlots * 256 / 4; i += kQBlock)
+      reinterpret_cast<uint32_t*>(&sm.map3[0][0])[i] = reinterpret_cast<const uint32_t*>(&qs->map3[0][0])[i];
+  __syncthreads();
+
+  const int cpr = K / 8;  // chunks per row
+  const int Gs = K >> gshift;
+  const int64_t total = N * (int64_t)cpr;
+  const int64_t begin = (int64_t)blockIdx.x * per_block;
+  int64_t end = begin + per_block;
+  if (end > total) end = total;
+  int64_t e = begin + tid;
+  int64_t row = e / cpr;
+  int c = (int)(e - row * cpr);
+  const int step_rows = kQBlock / cpr, step_c = kQBlock % cpr;
+  for (; e < end; e += kQBlock) {
+    const int col = c * 8;
+    const uint4 v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+    const float r = rinv[row * Gs + (col >> gshift)];
+    const W8 w = unpack8(v);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const uint32_t key = order_key(w.w[p] * r);
+      if (PASS == 1) {
+        atomicAdd(&sm.hist[key >> 20], 1u);
+      } else {
+        uint32_t s = sm.map1[key >> 20];
+        if (PASS >= 3 && s != 0xFFu) s = sm.map2[s][(key >> 12) & 0xFFu];
+        if (PASS >= 4 && s != 0xFFu) s = sm.map3[s][(key >> 4) & 0xFFu];
+        if (s != 0xFFu) {
+          const uint32_t bin = (key >> PassBits<PASS>::shift) & (uint32_t)(PassBits<PASS>::bins - 1);
+          atomicAdd(&sm.hist[s * PassBits<PASS>::bins + bin], 1u);
+        }
+      }
+    }
+    row += step_rows;
+    c += step_c;
+    if (c >= cpr) { c -= cpr; ++row; }
+  }
+  __syncthreads();
+  unsigned long long* out = PASS == 1 ? qs->hist1 : &qs->hist[0][0];
+  for (int i = tid; i < kCounters; i += kQBlock) {
+    const uint32_t n = sm.hist[i];
+    if (n != 0u) {
+      // pass 4 has 16 bins per slot; they are stored at the start of the slot's 256 counters
+      const int dst = PASS == 4 ? (i / 16) * 256 + (i % 16) : i;
+      atomicAdd(out + dst, (unsigned long long)n);
+    }
+  }
+}
+
+struct SelectLds {
+  unsigned long long cum[kQuantSlots * 256];  // pass 1: 4096 prefix sums; later: the staged histograms
+  unsigned long long lane_total[64];
+  unsigned long long rank[kQuantSlots];
+  uint32_t prefix[kQuantSlots];
+  uint32_t bin[kQuantSlots];
+  uint8_t slot[kQuantSlots];
+};
+
+// After histogram pass PASS: for every wanted rank find its bin, narrow the rank,
+// hand out the slots of the next pass and clear the counters.  One block.
+// After the last pass the keys are complete and the 32 table entries are written.
+template <int PASS>
+__global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __restrict__ qs, const QuantTargets tg,
+                                                               float* __restrict__ grid_out) {
+  __shared__ SelectLds sm;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int U = tg.count;
+  if (PASS == 1) {
+    // exclusive prefix sums of the 4096 counters: 64 lanes x 64 consecutive bins
+    for (int i = tid; i < 4096; i += kQBlock) sm.cum[i] = qs->hist1[i];
+    __syncthreads();
+    if (tid < 64) {
+      unsigned long long s = 0;
+      for (int j = 0; j < 64; ++j) {
+        const unsigned long long n = sm.cum[lane * 64 + j];
+        sm.cum[lane * 64 + j] = s;
+        s += n;
+      }
+      sm.lane_total[lane] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long s = 0;
+      for (int j = 0; j < 64; ++j) {
+        const unsigned long long n = sm.lane_total[j];
+        sm.lane_total[j] = s;
+        s += n;
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < 4096; i += kQBlock) sm.cum[i] += sm.lane_total[i / 64];
+    __syncthreads();
+    if (tid < U) {  // the last bin whose prefix sum does not exceed the rank
+      const unsigned long long rank = tg.rank[tid];
+      int lo = 0, hi = 4095;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (sm.cum[mid] <= rank) lo = mid; else hi = mid - 1;
+      }
+      sm.bin[tid] = (uint32_t)lo;
+      sm.prefix[tid] = (uint32_t)lo;
+      sm.rank[tid] = rank - sm.cum[lo];
+    }
+    for (int i = tid; i < 4096; i += kQBlock) { qs->hist1[i] = 0; qs->map1[i] = 0xFF; }
+  } else {
+    constexpr int kBins = PassBits<PASS>::bins;
+    for (int i = tid; i < kQuantSlots * 256; i += kQBlock) sm.cum[i] = (&qs->hist[0][0])[i];
+    if (tid < U) {
+      sm.rank[tid] = qs->rank[tid];
+      sm.prefix[tid] = qs->prefix[tid];
+      sm.slot[tid] = qs->slot[tid];
+    }
+    __syncthreads();
+    if (tid < U) {
+      const unsigned long long rank = sm.rank[tid];
+      const unsigned long long* h = sm.cum + (int)sm.slot[tid] * 256;
+      unsigned long long below = 0, taken = 0;
+      int bin = 0;
+      for (int b = 0; b < kBins; ++b) {  // the last bin whose prefix sum does not exceed the rank
+        if (below <= rank) { bin = b; taken = below; }
+        below += h[b];
+      }
+      sm.bin[tid] = (uint32_t)bin;
+      sm.prefix[tid] = (sm.prefix[tid] << (kBins == 16 ? 4 : 8)) | (uint32_t)bin;
+      sm.rank[tid] = rank - taken;
+    }
+    for (int i = tid; i < kQuantSlots * 256; i += kQBlock) {
+      (&qs->hist[0][0])[i] = 0;
+      if (PASS == 2) (&qs->map2[0][0])[i] = 0xFF;
+      if (PASS == 3) (&qs->map3[0][0])[i] = 0xFF;
+    }
+  }
+  __syncthreads();
+  if (PASS < 4) {
+    // ranks are ascending, so prefixes are too: a new slot starts where the prefix changes
+    if (tid == 0) {
+      int slots = 0;
+      for (int u = 0; u < U; ++u) {
+        if (u == 0 || sm.prefix[u] != sm.prefix[u - 1]) ++slots;
+        const uint8_t s = (uint8_t)(slots - 1);
+        if (PASS == 1) qs->map1[sm.bin[u]] = s;
+        if (PASS == 2) qs->map2[sm.slot[u]][sm.bin[u]] = s;
+        if (PASS == 3) qs->map3[sm.slot[u]][sm.bin[u]] = s;
+        qs->slot[u] = s;
+        qs->rank[u] = sm.rank[u];
+        qs->prefix[u] = sm.prefix[u];
+      }
+    }
+  } else if (tid < 32) {
+    // the prefixes are the full keys now: interpolate the 32 quantiles
+    const QuantLevel q = tg.level[tid];
+    double v = (double)key_value(sm.prefix[q.lo]);
+    if (q.rem != 0u) {
+      const double frac = (double)q.rem / (double)q.den;
+      v = v + frac * ((double)key_value(sm.prefix[q.hi]) - v);
+    }
+    grid_out[tid] = (float)v + 0.0f;  // a zero is stored as +0
+  }
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+QuantTargets make_quant_targets(int64_t N, int64_t K) {
+  QuantTargets tg = {};
+  const unsigned __int128 last = (unsigned __int128)N * (unsigned __int128)K - 1;
+  unsigned long long lo[32], rem[32];
+  for (int t = 0; t < 2; ++t)
+    for (int i = 0; i < 16; ++i) {
+      const unsigned __int128 num = t == 0 ? i : 15 + 29 * i, den = t == 0 ? 15 : 450;
+      const unsigned __int128 pos = num * last;
+      lo[16 * t + i] = (unsigned long long)(pos / den);
+      rem[16 * t + i] = (unsigned long long)(pos % den);
+      tg.level[16 * t + i].rem = (uint32_t)rem[16 * t + i];
+      tg.level[16 * t + i].den = (uint32_t)den;
+    }
+  // the wanted ranks, ascending and without repeats (levels ascend inside a table, the two tables interleave)
+  unsigned long long all[64];
+  int n = 0;
+  for (int q = 0; q < 32; ++q) {
+    all[n++] = lo[q];
+    if (rem[q] != 0) all[n++] = lo[q] + 1;
+  }
+  for (int i = 1; i < n; ++i) {  // insertion sort
+    const unsigned long long v = all[i];
+    int j = i - 1;
+    while (j >= 0 && all[j] > v) { all[j + 1] = all[j]; --j; }
+    all[j + 1] = v;
+  }
+  int U = 0;
+  for (int i = 0; i < n; ++i)
+    if (U == 0 || tg.rank[U - 1] != all[i]) tg.rank[U++] = all[i];
+  tg.count = U;
+  auto find = [&](unsigned long long r) {
+    for (int u = 0; u < U; ++u)
+      if (tg.rank[u] == r) return u;
+    return 0;
+  };
+  for (int q = 0; q < 32; ++q) {
+    tg.level[q].lo = (uint8_t)find(lo[q]);
+    tg.level[q].hi = (uint8_t)(rem[q] != 0 ? find(lo[q] + 1) : tg.level[q].lo);
+  }
+  return tg;
+}
+
+hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size,
+                                const float* rinv, void* quant_state, float* grid_out, hipStream_t stream) {
+  QuantState* qs = static_cast<QuantState*>(quant_state);
+  const uint16_t* Wp = static_cast<const uint16_t*>(W);
+  int gshift = 0;
+  for (int g = group_size; g > 1; g >>= 1) ++gshift;
+  const QuantTargets tg = make_quant_targets(N, K);
+  // counters start at zero (the select kernels clear them again after each pass)
+  hipError_t e = launch_fill_zero(qs, offsetof(QuantState, map1), stream);
+  if (e != hipSuccess) return e;
+  const int64_t chunks = N * (K / 8);
+  int64_t blocks = ceil_div(chunks, 4 * kQBlock);  // at least four chunks per thread
+  if (blocks > 512) blocks = 512;
+  const int64_t per_block = ceil_div(ceil_div(chunks, blocks), kQBlock) * kQBlock;
+  blocks = ceil_div(chunks, per_block);
+#define AAAC_QPASS(P)                                                                                          \
+  quant_hist_kernel<P><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, qs); \
+  if ((e = hipGetLastError()) != hipSuccess) return e;                                                         \
+  quant_select_kernel<P><<<1, kQBlock, 0, stream>>>(qs, tg, grid_out);                                         \
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  AAAC_QPASS(1)
+  AAAC_QPASS(2)
+  AAAC_QPASS(3)
+  AAAC_QPASS(4)
+#undef AAAC_QPASS
+  return hipSuccess;
+}
+
+}  // namespace aaac

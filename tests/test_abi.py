@@ -107,6 +107,17 @@ def test_other_entry_points_validate():
     assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, 1 << 20, 1 << 20, FAKE, 1 << 20, None) == E_ARG  # pass count overflows
     assert L.aaac_fit_nested(arr, 1, 16, 16, 0, gp, 2, 2, FAKE, 16, None) == E_WS
     assert L.aaac_fit_nested_workspace(arr, 1, 16, 16, 0) == L.aaac_fit_batch_workspace(arr, 1, 16, 0) > 0
+    # quantile initialisation
+    assert L.aaac_quantile_init(None, 8, 64, 64, 16, 0, FAKE, FAKE, 1 << 22, None) == E_NULL
+    assert L.aaac_quantile_init(FAKE, 8, 64, 64, 16, 0, None, FAKE, 1 << 22, None) == E_NULL
+    assert L.aaac_quantile_init(FAKE, 0, 64, 64, 16, 0, FAKE, FAKE, 1 << 22, None) == E_SHAPE   # no weights
+    assert L.aaac_quantile_init(FAKE, 8, 72, 72, 16, 0, FAKE, FAKE, 1 << 22, None) == E_SHAPE
+    assert L.aaac_quantile_init(FAKE, 8, 64, 64, 16, 4, FAKE, FAKE, 1 << 22, None) == E_ARG
+    assert L.aaac_quantile_init(FAKE, 8, 64, 64, 16, 0, FAKE, FAKE, 64, None) == E_WS
+    assert L.aaac_quantile_init_workspace(8, 64, 16, 0) == L.aaac_fit_workspace(8, 64, 16, 0)
+    empty = (A.binding.aaac_layer_t * 1)(A.binding.aaac_layer_t(None, 0, 64, 64, 0x10000, None, 0x10000, None))
+    assert L.aaac_fit_nested(empty, 1, 16, 16, 0, None, 1, 1, FAKE, 1 << 22, None) == E_SHAPE  # quantiles of nothing
+    assert L.aaac_fit_batch(arr, 1, 16, 0, None, 1, FAKE, 1 << 22, None) == E_NULL
     # selection groups: a size that divides the scale group, 16..128
     assert L.aaac_fit_nested(arr, 1, 16, 32, 0, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE  # larger than the scale group
     assert L.aaac_fit_nested(arr, 1, 64, 8, 1, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE

@@ -492,6 +492,83 @@ def test_selection_groups_cfg1_shape_full_size():
     assert ref["objective"][-1] < coarse["objective"][-1]
 
 
+# ------------------------------------------ quantile initialisation
+
+def u32(a):
+    return np.ascontiguousarray(a, np.float32).view(np.uint32)
+
+
+@pytest.mark.parametrize("N,K,g,fmt,kind", [
+    (64, 512, 16, 0, "gauss_outlier"),
+    (130, 1536, 128, 1, "gauss_outlier"),
+    (37, 1040, 16, 0, "student5"),
+    (1, 16, 16, 0, "gauss_outlier"),        # 16 weights: every level falls between two of them
+    (3, 32, 32, 1, "gauss_outlier"),
+    (200, 4096, 128, 1, "gauss_outlier"),
+    (1030, 2048, 64, 1, "student5"),        # more chunks than one block takes
+])
+def test_quantile_init_matches_oracle(N, K, g, fmt, kind):
+    say(f"[quantile] N={N} K={K} g={g} fmt={fmt} {kind}")
+    Wt = inputs.make_weight(N, K, kind, 600 + N + K, DEV)
+    grid = A.aaac_quantile_init(Wt, g, fmt)
+    torch.cuda.synchronize()
+    ref = oracle.quantile_init(inputs.bits(Wt), g, fmt)
+    assert (u32(host(grid)) == u32(ref)).all()
+
+
+def test_quantile_init_degenerate_weights_and_padded_rows():
+    # all weights zero, some of them -0.0: every normalised weight is a zero, the tables are +0
+    Wz = torch.zeros((40, 256), dtype=torch.bfloat16, device=DEV)
+    Wz[::3] = -0.0
+    grid = A.aaac_quantile_init(Wz, 16, A.NVFP4)
+    torch.cuda.synchronize()
+    assert (u32(host(grid)) == 0).all()
+    assert (u32(oracle.quantile_init(inputs.bits(Wz), 16, A.NVFP4)) == 0).all()
+    # two distinct values only: long runs of equal keys
+    Wt = torch.where(torch.rand((64, 512), device=DEV) < 0.3, 0.05, -0.02).to(torch.bfloat16)
+    grid = A.aaac_quantile_init(Wt, 128, A.INT4)
+    torch.cuda.synchronize()
+    assert (u32(host(grid)) == u32(oracle.quantile_init(inputs.bits(Wt), 128, A.INT4))).all()
+    # rows with a padded leading dimension; the padding holds large values that must not be read
+    big = torch.full((50, 768), 100.0, dtype=torch.bfloat16, device=DEV)
+    Wp = big[:, :640]
+    Wp.copy_(inputs.make_weight(50, 640, "gauss_outlier", 77, DEV))
+    grid = A.aaac_quantile_init(Wp, 64, A.INT4)
+    torch.cuda.synchronize()
+    assert (u32(host(grid)) == u32(oracle.quantile_init(inputs.bits(Wp.contiguous()), 64, A.INT4))).all()
+
+
+def test_fit_from_quantile_tables_matches_oracle():
+    # init_grid = NULL: Alg. 1 as printed, quantile tables then both loops, also with S < g and in a batch
+    shapes = [(96, 1024), (40, 512), (128, 1536)]
+    g, S, fmt = 128, 16, A.INT4
+    Ws = [inputs.make_weight(N, K, "gauss_outlier", 700 + i, DEV) for i, (N, K) in enumerate(shapes)]
+    Is = [torch.rand(K, device=DEV) * 10 + 0.05 for _, K in shapes]
+    outs = nested_on_gpu(Ws, Is, g, fmt, None, 3, 2, S=S)
+    for W, I, (tf, tb, ob) in zip(Ws, Is, outs):
+        q = oracle.quantile_init(inputs.bits(W), g, fmt)
+        ref = oracle.fit_sel(inputs.bits(W), g, S, fmt, host(I), q, 3, 2)
+        assert (u16(tb) == ref["tables_bf16"]).all()
+        assert tables_close(host(tf), ref["tables_f32"])
+        assert np.allclose(host(ob)[:3], ref["objective"], rtol=1e-9)
+    # zero outer steps: the tables that come back are the quantile tables themselves
+    (tf, tb, ob), = nested_on_gpu(Ws[:1], Is[:1], g, fmt, None, 0, 1)
+    assert (u32(host(tf)) == u32(oracle.quantile_init(inputs.bits(Ws[0]), g, fmt))).all()
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2])
+def test_quantile_init_full_size(cfg_id):
+    cfg = inputs.CONFIGS[cfg_id]
+    l = cfg["layers"][0]
+    Wt = inputs.layer_weights(l, DEV)
+    grid = A.aaac_quantile_init(Wt, cfg["g"], cfg["fmt"])
+    torch.cuda.synchronize()
+    t0 = time.time()
+    ref = oracle.quantile_init(inputs.bits(Wt), cfg["g"], cfg["fmt"])
+    say(f"[quantile] cfg{cfg_id} oracle {time.time() - t0:.1f}s")
+    assert (u32(host(grid)) == u32(ref)).all()
+
+
 # ------------------------------------------ benchmark settings, full size
 
 def test_config0_full():

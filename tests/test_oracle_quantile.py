@@ -109,3 +109,10 @@ def test_quantile_tables_differ_so_both_are_used_from_the_first_assignment():
     assert same.sum() == 0
     a = oracle.fit_nested(W, g, fmt, I, q, 4, 2)
     assert (np.diff(a["objective"]) <= 0).all()
+
+
+def test_zero_results_are_positive_zero():
+    # every weight is -0.0: the normalised weights are -0.0, the tables must hold +0.0
+    W = np.full((2, 16), 0x8000, np.uint16)
+    grid = oracle.quantile_init(W, 16, oracle.NVFP4)
+    assert (grid.view(np.uint32) == 0).all()
