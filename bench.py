@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--sel-size", type=int, default=None,
                     help="weights per table choice when smaller than the scale group (selection bits stored "
                          "separately); the fit then goes through aaac_fit_nested")
+    ap.add_argument("--quantile-init", action="store_true",
+                    help="start from the quantile tables of Alg. 1 (computed on the GPU inside the fit) instead of "
+                         "the format grid; the fit then goes through aaac_fit_nested")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -79,8 +82,9 @@ def main():
     warmup = args.warmup if args.warmup is not None else (1 if big else 3)
     g, fmt, iters = cfg["g"], cfg["fmt"], cfg["iters"]
     grid = inputs.format_grid(fmt)
+    fit_grid = None if args.quantile_init else grid   # None: quantile tables, taken on the GPU inside the fit
     S = args.sel_size if args.sel_size is not None else g
-    nested = args.n_inner > 1 or S != g
+    nested = args.n_inner > 1 or S != g or args.quantile_init
     n_outer = args.n_outer if args.n_outer is not None else (3 if args.n_inner > 1 else iters)
     n_inner = args.n_inner
     iters = n_outer  # length of the objective trace
@@ -123,7 +127,7 @@ def main():
             A.aaac_act_stats(X, Is[k], ws_stats[k], stream)
         mark(1)
         if nested:
-            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, n_inner, ws_batch, stream, sel_size=S)
+            A.aaac_fit_nested(arr, g, fmt, fit_grid, n_outer, n_inner, ws_batch, stream, sel_size=S)
         elif batch:
             A.aaac_fit_batch(arr, g, fmt, grid, iters, ws_batch, stream)
         else:
@@ -162,19 +166,38 @@ def main():
     weights_per_s_iter = n_w / (iter_us * 1e-6)
     value = n_w * passes / (ms_per_step * 1e-3)
 
+    q_ms, quant = 0.0, None
+    if args.quantile_init:
+        # the initialisation alone (it is inside `fit` above): four histogram passes over the weights
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        qg = torch.empty(32, dtype=torch.float32, device=dev)
+        for L in layers:
+            A.aaac_quantile_init(L["W"], g, fmt, qg, L["ws"], stream)
+        e0.record(stream)
+        for _ in range(5):
+            for L in layers:
+                A.aaac_quantile_init(L["W"], g, fmt, qg, L["ws"], stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        q_ms = e0.elapsed_time(e1) / 5
+        q_gbs = 4 * bytes_per_weight(g) * n_w / (q_ms * 1e-3) / 1e9
+        quant = {"ms": q_ms, "passes_over_weights": 4, "hbm_achieved_GBs": q_gbs, "hbm_frac": q_gbs / HBM_PEAK_GBS}
+        iter_us = (fit_ms - q_ms) * 1e3 / passes
+        weights_per_s_iter = n_w / (iter_us * 1e-6)
+
     refine = None
     if n_inner > 1:
         # refinement pass alone: the same fit with one inner step costs n_outer assignment passes
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = max(steps, 3)
-        A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream, sel_size=S)
+        A.aaac_fit_nested(arr, g, fmt, fit_grid, n_outer, 1, ws_batch, stream, sel_size=S)
         e0.record(stream)
         for _ in range(reps):
-            A.aaac_fit_nested(arr, g, fmt, grid, n_outer, 1, ws_batch, stream, sel_size=S)
+            A.aaac_fit_nested(arr, g, fmt, fit_grid, n_outer, 1, ws_batch, stream, sel_size=S)
         e1.record(stream)
         torch.cuda.synchronize()
-        assign_ms = e0.elapsed_time(e1) / reps
-        refine_us = (fit_ms - assign_ms) * 1e3 / (n_outer * (n_inner - 1))
+        assign_ms = e0.elapsed_time(e1) / reps - q_ms   # these fits include the initialisation
+        refine_us = (fit_ms - q_ms - assign_ms) * 1e3 / (n_outer * (n_inner - 1))
         ops = LANE_OPS_PER_WEIGHT_REFINE * n_w / (refine_us * 1e-6) / 1e12
         refine = {"kernel": "lloyd_iter_kernel (choice frozen)", "assign_pass_us": assign_ms * 1e3 / n_outer,
                   "refine_pass_us": refine_us, "weights_per_s": n_w / (refine_us * 1e-6), "bound": "alu",
@@ -227,6 +250,9 @@ def main():
 
     if refine is not None:
         out["refine_roofline"] = refine
+    if quant is not None:
+        out["quantile_init"] = quant
+        out["config"]["init"] = "quantile"
 
     if not args.no_cpu_baseline:
         import oracle
@@ -237,7 +263,8 @@ def main():
         Ih = Is[L["x"]].cpu().numpy()
         t1 = time.perf_counter()
         if nested:
-            oracle.fit_sel(Wb, g, S, fmt, Ih, grid, n_outer, n_inner)
+            g0 = oracle.quantile_init(Wb, g, fmt) if args.quantile_init else grid
+            oracle.fit_sel(Wb, g, S, fmt, Ih, g0, n_outer, n_inner)
         else:
             oracle.fit(Wb, g, fmt, Ih, grid, iters)
         dt = time.perf_counter() - t1

@@ -115,6 +115,7 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
 struct SelectLds {
   unsigned long long cum[kQuantSlots * 256];  // pass 1: 4096 prefix sums; later: the staged histograms
   unsigned long long lane_total[64];
+  unsigned long long part[kQuantSlots][16];
   unsigned long long rank[kQuantSlots];
   uint32_t prefix[kQuantSlots];
   uint32_t bin[kQuantSlots];
@@ -166,49 +167,77 @@ __global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __res
       sm.prefix[tid] = (uint32_t)lo;
       sm.rank[tid] = rank - sm.cum[lo];
     }
-    for (int i = tid; i < 4096; i += kQBlock) { qs->hist1[i] = 0; qs->map1[i] = 0xFF; }
+    for (int i = tid; i < 4096; i += kQBlock) qs->hist1[i] = 0;
+    for (int i = tid; i < 4096 / 4; i += kQBlock) reinterpret_cast<uint32_t*>(qs->map1)[i] = 0xFFFFFFFFu;
   } else {
     constexpr int kBins = PassBits<PASS>::bins;
-    for (int i = tid; i < kQuantSlots * 256; i += kQBlock) sm.cum[i] = (&qs->hist[0][0])[i];
+    // slots are handed out in ascending order, so the last target holds the highest one in use
+    const int used = (int)qs->slot[U - 1] + 1;
+    for (int i = tid; i < used * kBins; i += kQBlock) {
+      const int at = (i / kBins) * 256 + (i % kBins);
+      sm.cum[at] = (&qs->hist[0][0])[at];
+      (&qs->hist[0][0])[at] = 0;
+    }
     if (tid < U) {
       sm.rank[tid] = qs->rank[tid];
       sm.prefix[tid] = qs->prefix[tid];
       sm.slot[tid] = qs->slot[tid];
     }
     __syncthreads();
-    if (tid < U) {
-      const unsigned long long rank = sm.rank[tid];
-      const unsigned long long* h = sm.cum + (int)sm.slot[tid] * 256;
-      unsigned long long below = 0, taken = 0;
-      int bin = 0;
-      for (int b = 0; b < kBins; ++b) {  // the last bin whose prefix sum does not exceed the rank
-        if (below <= rank) { bin = b; taken = below; }
-        below += h[b];
+    // 16 threads per target: thread j adds up bins [j * kBins/16, (j + 1) * kBins/16) of the
+    // target's slot, then the group's first thread walks the 16 partial sums and the one
+    // segment that holds the rank
+    {
+      constexpr int kSeg = kBins / 16;
+      const int u = tid >> 4, j = tid & 15;
+      const bool live = u < U;
+      const unsigned long long* h = sm.cum + (live ? (int)sm.slot[u] : 0) * 256;
+      unsigned long long part = 0;
+#pragma unroll
+      for (int b = 0; b < kSeg; ++b) part += h[j * kSeg + b];
+      sm.part[u][j] = part;
+      __syncthreads();
+      if (live && j == 0) {
+        const unsigned long long rank = sm.rank[u];
+        unsigned long long below = 0, taken = 0;
+        int seg = 0;
+        for (int k = 0; k < 16; ++k) {  // the last segment whose prefix sum does not exceed the rank
+          if (below <= rank) { seg = k; taken = below; }
+          below += sm.part[u][k];
+        }
+        below = taken;
+        int bin = seg * kSeg;
+        for (int b = 0; b < kSeg; ++b) {  // and the last such bin inside it
+          if (below <= rank) { bin = seg * kSeg + b; taken = below; }
+          below += h[seg * kSeg + b];
+        }
+        sm.bin[u] = (uint32_t)bin;
+        sm.prefix[u] = (sm.prefix[u] << (kBins == 16 ? 4 : 8)) | (uint32_t)bin;
+        sm.rank[u] = rank - taken;
       }
-      sm.bin[tid] = (uint32_t)bin;
-      sm.prefix[tid] = (sm.prefix[tid] << (kBins == 16 ? 4 : 8)) | (uint32_t)bin;
-      sm.rank[tid] = rank - taken;
     }
-    for (int i = tid; i < kQuantSlots * 256; i += kQBlock) {
-      (&qs->hist[0][0])[i] = 0;
-      if (PASS == 2) (&qs->map2[0][0])[i] = 0xFF;
-      if (PASS == 3) (&qs->map3[0][0])[i] = 0xFF;
+    for (int i = tid; i < kQuantSlots * 256 / 4; i += kQBlock) {
+      if (PASS == 2) reinterpret_cast<uint32_t*>(&qs->map2[0][0])[i] = 0xFFFFFFFFu;
+      if (PASS == 3) reinterpret_cast<uint32_t*>(&qs->map3[0][0])[i] = 0xFFFFFFFFu;
     }
   }
   __syncthreads();
   if (PASS < 4) {
-    // ranks are ascending, so prefixes are too: a new slot starts where the prefix changes
-    if (tid == 0) {
-      int slots = 0;
-      for (int u = 0; u < U; ++u) {
-        if (u == 0 || sm.prefix[u] != sm.prefix[u - 1]) ++slots;
-        const uint8_t s = (uint8_t)(slots - 1);
-        if (PASS == 1) qs->map1[sm.bin[u]] = s;
-        if (PASS == 2) qs->map2[sm.slot[u]][sm.bin[u]] = s;
-        if (PASS == 3) qs->map3[sm.slot[u]][sm.bin[u]] = s;
-        qs->slot[u] = s;
-        qs->rank[u] = sm.rank[u];
-        qs->prefix[u] = sm.prefix[u];
+    // ranks are ascending, so prefixes are too: a new slot starts where the prefix changes.
+    // The targets are the lanes of the first wavefront; targets that share a prefix write
+    // the same slot to the same map entry.
+    if (tid < 64) {
+      const bool live = tid < U;
+      const bool opens = live && (tid == 0 || sm.prefix[tid] != sm.prefix[tid - 1]);
+      const uint64_t opened = __builtin_amdgcn_ballot_w64(opens);
+      if (live) {
+        const uint8_t s = (uint8_t)(__builtin_popcountll(opened & (~0ull >> (63 - tid))) - 1);
+        if (PASS == 1) qs->map1[sm.bin[tid]] = s;
+        if (PASS == 2) qs->map2[sm.slot[tid]][sm.bin[tid]] = s;
+        if (PASS == 3) qs->map3[sm.slot[tid]][sm.bin[tid]] = s;
+        qs->slot[tid] = s;
+        qs->rank[tid] = sm.rank[tid];
+        qs->prefix[tid] = sm.prefix[tid];
       }
     }
   } else if (tid < 32) {
