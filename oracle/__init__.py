@@ -70,6 +70,8 @@ def lib():
         L.oracle_dequant_sel.argtypes = [_P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64]
         L.oracle_quantile_init.restype = _INT
         L.oracle_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P]
+        L.oracle_gemv_w4a16.restype = _INT
+        L.oracle_gemv_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _P]
         L.oracle_encode.restype = _INT
         L.oracle_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P]
         L.oracle_dequant.restype = _INT
@@ -293,3 +295,22 @@ def quantile_init(W_bits, g, fmt):
     grid = np.empty(32, np.float32)
     _check(lib().oracle_quantile_init(_ptr(W), N, K, K, g, fmt, _ptr(grid)), "quantile_init")
     return grid
+
+
+def gemv_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt):
+    """y = x W^^T with the quantised layer: x_bits uint16 [M, K] (bf16) -> (y float32 [M, N],
+    abs_sum float64 [M, N] = sum_k |x * w^|)."""
+    x = _c(x_bits, np.uint16)
+    M, K = x.shape
+    codes = _c(codes, np.uint8)
+    N = codes.shape[0]
+    assert codes.shape[1] * 2 == K
+    scales = _c(scales, _scale_dtype(fmt))
+    tb = _c(tables_bf16, np.uint16).reshape(32)
+    bits = None if sel_bits is None else _c(sel_bits, np.uint8)
+    y = np.empty((M, N), np.float32)
+    mag = np.empty((M, N), np.float64)
+    _check(lib().oracle_gemv_w4a16(_ptr(x), M, K, _ptr(codes), _ptr(scales), _ptr(bits),
+                                   0 if bits is None else bits.shape[1], _ptr(tb), N, K, g, S, fmt,
+                                   _ptr(y), _ptr(mag)), "gemv_w4a16")
+    return y, mag

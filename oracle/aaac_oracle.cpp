@@ -596,4 +596,53 @@ int oracle_quantile_init(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, i
   return 0;
 }
 
+// ---------------------------------------------------------------------------
+// The quantised layer applied to activations (W4A16: 4-bit weights, 16-bit
+// activations): y[m, n] = sum_k x[m, k] * w^[n, k] with the dequantised weight
+// of Eq. "aaac_dequant", w^ = T_sigma[code] * s, taken as the real product (a
+// fused kernel never stores w^, so there is no bf16 rounding of it).  x, the
+// table entries and the scale carry 8 significant bits each, so every term is
+// exact in fp64; the sum is compensated and rounded once to fp32.
+// abs_sum (optional, [M x N]) receives sum_k |x * w^|, the quantity a
+// floating-point summation error bound is stated against.
+// sel_bits / S as in oracle_dequant_sel.
+int oracle_gemv_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                      const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                      int64_t N, int64_t K, int g, int S, int fmt, float* y, double* abs_sum) {
+  if (!valid_shape(N, K, K, g) || !valid_shape(N, K, K, S) || S > g || M < 0 || ldx < K) return -1;
+  if (S < g && !sel_bits) return -1;
+  int64_t G = K / g;
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      Sum acc, mag;
+      for (int64_t k = 0; k < K; ++k) {
+        int64_t j = k / g;
+        int sigma;
+        float s;
+        if (fmt == FMT_NVFP4) {
+          uint8_t c = static_cast<const uint8_t*>(scales)[n * G + j];
+          sigma = c >> 7;
+          s = e4m3_to_f32(c & 0x7F);
+        } else {
+          uint16_t c = static_cast<const uint16_t*>(scales)[n * G + j];
+          sigma = c >> 15;
+          s = bf16_to_f32(c & 0x7FFF);
+        }
+        if (S < g) {
+          int64_t sel = k / S;
+          sigma = (sel_bits[n * sel_stride + sel / 8] >> (sel % 8)) & 1;
+        }
+        uint8_t byte = codes[(n * K + k) / 2];
+        int code = (k & 1) ? (byte >> 4) : (byte & 15);
+        long double t = static_cast<long double>(bf16_to_f32(tables_bf16[16 * sigma + code])) *
+                        static_cast<long double>(s) * static_cast<long double>(bf16_to_f32(x[m * ldx + k]));
+        acc.add(t);
+        mag.add(std::fabs(t));
+      }
+      y[m * N + n] = static_cast<float>(static_cast<double>(acc.value()));
+      if (abs_sum) abs_sum[m * N + n] = static_cast<double>(mag.value());
+    }
+  return 0;
+}
+
 }  // extern "C"
