@@ -186,6 +186,29 @@ int aaac_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* se
                      int group_size, int sel_size, aaac_format_t fmt, void* W_hat, int64_t ldo,
                      void* hip_stream);
 
+/* ---- The quantised layer applied to activations, W4A16 (paper Eq. "pipeline": the
+ * dequantised values w^ = T[c] * s are the weights used at inference; Eq. "aaac_dequant"
+ * with the two tables):
+ *   y[m, n] = sum_k x[m, k] * T_sigma[code[n, k]] * s[n, k / group_size]
+ * computed from the codes, scales (and selection bits) as aaac_encode / aaac_encode_sel
+ * write them; the dequantised weights are never stored and w^ is the real product (no
+ * bf16 rounding of it).  Arithmetic: fp32 FMAs, every term exact; only the order of the
+ * additions differs from exact evaluation: at most 22 + 4 * ceil(K / 2048) roundings lie
+ * on the path of a term, so |error| <= (22 + 4 * ceil(K / 2048)) * 2^-24 * sum_k |x w^|
+ * to first order.
+ * Meant for a few rows of x (decode); x is taken four rows at a time, so larger M
+ * re-reads the codes M/4 times.
+ *   x        dev bf16 [M x ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned
+ *   codes    dev u8 [N x K/2] dense, 16-byte aligned; K % 32 == 0
+ *   scales, sel_bits, sel_stride, tables_bf16, group_size, sel_size, fmt: as aaac_dequant_sel
+ *            (scales 4-byte aligned)
+ *   y        dev fp32 [M x ldy], ldy >= N, overwritten
+ * Errors as aaac_dequant_sel; K % 32 != 0 is AAAC_ERR_SHAPE. */
+int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                    const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
+                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
+                    void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

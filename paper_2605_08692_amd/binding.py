@@ -66,6 +66,8 @@ def library():
         L.aaac_quantile_init_workspace.argtypes = [_I64, _I64, _INT, _INT]
         L.aaac_quantile_init.restype = _INT
         L.aaac_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _SZ, _P]
+        L.aaac_gemv_w4a16.restype = _INT
+        L.aaac_gemv_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64, _P]
         L.aaac_encode_sel.restype = _INT
         L.aaac_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64, _P]
         L.aaac_dequant_sel.restype = _INT
@@ -277,3 +279,19 @@ def aaac_quantile_init(W, group_size, fmt, grid=None, ws=None, stream=None):
     _check(library().aaac_quantile_init(_dp(W), N, K, ldw, group_size, fmt, _dp(grid), _dp(ws), ws.numel(),
                                         _stream(stream)), "aaac_quantile_init")
     return grid
+
+
+def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None):
+    """x bf16 [M, K] times the quantised layer -> y fp32 [M, N]."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    M, K = x.shape
+    N = codes.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    ldx = x.stride(0) if M > 1 else max(x.stride(0), K)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
+    _check(library().aaac_gemv_w4a16(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
+                                     _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy,
+                                     _stream(stream)), "aaac_gemv_w4a16")
+    return y

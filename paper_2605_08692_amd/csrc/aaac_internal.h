@@ -105,4 +105,11 @@ hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_
                           int group_size, int sel_size, int fmt, void* W_hat, int64_t ldo,
                           hipStream_t stream);
 
+constexpr int kGemvMaxRows = 128;  // output rows one block of the W4A16 product accumulates
+// y[M x ldy] fp32 = x[M x ldx] bf16 times the quantised layer (codes, scales, tables), K % 32 == 0.
+hipError_t launch_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                             const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                             int64_t N, int64_t K, int group_size, int sel_size, int fmt, float* y, int64_t ldy,
+                             hipStream_t stream);
+
 }  // namespace aaac

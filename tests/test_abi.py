@@ -118,6 +118,17 @@ def test_other_entry_points_validate():
     empty = (A.binding.aaac_layer_t * 1)(A.binding.aaac_layer_t(None, 0, 64, 64, 0x10000, None, 0x10000, None))
     assert L.aaac_fit_nested(empty, 1, 16, 16, 0, None, 1, 1, FAKE, 1 << 22, None) == E_SHAPE  # quantiles of nothing
     assert L.aaac_fit_batch(arr, 1, 16, 0, None, 1, FAKE, 1 << 22, None) == E_NULL
+    # the quantised layer applied to activations
+    gemv = lambda **kw: L.aaac_gemv_w4a16(*[kw.get(k, d) for k, d in (
+        ("x", FAKE), ("M", 2), ("ldx", 128), ("codes", FAKE), ("scales", FAKE), ("bits", None), ("stride", 0),
+        ("tb", FAKE), ("N", 8), ("K", 128), ("g", 16), ("S", 16), ("fmt", 0), ("y", FAKE), ("ldy", 8), ("st", None))])
+    assert gemv(x=None) == E_NULL and gemv(y=None) == E_NULL and gemv(tb=None) == E_NULL
+    assert gemv(K=144, ldx=144) == E_SHAPE            # a multiple of the group size but not of 32
+    assert gemv(ldx=120) == E_SHAPE and gemv(ldy=4) == E_SHAPE
+    assert gemv(g=64, S=16) == E_NULL                 # selection bits needed
+    assert gemv(g=64, S=16, bits=FAKE, stride=0) == E_SHAPE
+    assert gemv(fmt=9) == E_ARG
+    assert gemv(codes=ctypes.c_void_p(0x10008)) == E_SHAPE   # codes not 16-byte aligned
     # selection groups: a size that divides the scale group, 16..128
     assert L.aaac_fit_nested(arr, 1, 16, 32, 0, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE  # larger than the scale group
     assert L.aaac_fit_nested(arr, 1, 64, 8, 1, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE

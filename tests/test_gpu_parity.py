@@ -569,6 +569,90 @@ def test_quantile_init_full_size(cfg_id):
     assert (u32(host(grid)) == u32(ref)).all()
 
 
+# ------------------------------------------ the quantised layer applied to activations (W4A16)
+
+def gemv_tolerance(K, mag):
+    """First-order bound on the fp32 summation error: roundings on the path of one term
+    (16 FMAs of the half-group sum, 2 for the scale, 4 lane-exchange adds, 4 adds per slab of 2048
+    columns into the row sum) times the unit roundoff times sum |terms|."""
+    return (22 + 4 * -(-K // 2048)) * 2.0 ** -24 * mag + 1e-30
+
+
+def quantise_on_gpu(Wt, I, g, S, fmt, iters=2):
+    (tf, tb, ob), = nested_on_gpu([Wt], [I], g, fmt, inputs.format_grid(fmt), iters, 1, S=S)
+    codes, scales, bits = A.aaac_encode_sel(Wt, g, S, fmt, I, tb)
+    torch.cuda.synchronize()
+    return tb, codes, scales, bits
+
+
+@pytest.mark.parametrize("N,K,g,S,fmt,M", [
+    (256, 512, 16, 16, 0, 1),       # a quarter slab
+    (130, 4096, 128, 128, 1, 1),    # two slabs, odd row count
+    (77, 2080, 16, 16, 0, 3),       # ragged last slab, three rows of x (four held, one zero)
+    (64, 4096, 128, 16, 1, 2),      # selection bits read from the bit array
+    (40, 6144, 64, 32, 1, 4),       # three slabs: two wavefronts of the block stay idle
+    (300, 18432, 32, 32, 0, 5),     # nine slabs (wavefronts take a second slab), x in two batches
+    (9, 1024, 16, 16, 1, 7),        # bf16 scales with groups of 16 (two per lane)
+])
+def test_gemv_w4a16_matches_oracle(N, K, g, S, fmt, M):
+    say(f"[gemv] N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
+    Wt = inputs.make_weight(N, K, "gauss_outlier", 800 + N + K, DEV)
+    I = torch.rand(K, device=DEV) + 0.05
+    tb, codes, scales, bits = quantise_on_gpu(Wt, I, g, S, fmt)
+    x = (torch.randn((M, K), device=DEV) * 2).to(torch.bfloat16)
+    y = A.aaac_gemv_w4a16(x, codes, scales, bits, tb, g, S, fmt)
+    torch.cuda.synchronize()
+    ref, mag = oracle.gemv_w4a16(inputs.bits(x), host(codes), host(scales).view(np.uint8 if fmt == 0 else np.uint16),
+                                 None if bits is None else host(bits), u16(tb), g, S, fmt)
+    err = np.abs(host(y).astype(np.float64) - ref)
+    assert (err <= gemv_tolerance(K, mag) + np.spacing(np.abs(ref))).all(), float((err / (mag + 1e-30)).max())
+    # and it is the product with the dequantised layer, up to the bf16 rounding of the stored weights
+    What = A.aaac_dequant_sel(codes, scales, bits, tb, g, S, fmt).double()
+    torch.cuda.synchronize()
+    assert np.abs(host(y) - host(x.double() @ What.T)).max() <= 2.0 ** -8 * mag.max()
+
+
+def test_gemv_w4a16_unit_vectors_and_strides():
+    # x = e_k returns column k of the dequantised layer exactly; padded x and y rows
+    N, K, g, fmt = 48, 256, 16, 0
+    Wt = inputs.make_weight(N, K, "student5", 31, DEV)
+    I = torch.rand(K, device=DEV) + 0.05
+    tb, codes, scales, bits = quantise_on_gpu(Wt, I, g, g, fmt)
+    xbig = torch.zeros((4, K + 64), dtype=torch.bfloat16, device=DEV)
+    xbig[:, K:] = 100.0                       # padding that must not be read
+    x = xbig[:, :K]
+    for m, k in enumerate((0, 17, 130, 255)):
+        x[m, k] = 1.0
+    ybig = torch.full((4, N + 8), -7.0, dtype=torch.float32, device=DEV)
+    y = A.aaac_gemv_w4a16(x, codes, scales, bits, tb, g, g, fmt, y=ybig[:, :N])
+    What = A.aaac_dequant(codes, scales, tb, g, fmt)
+    torch.cuda.synchronize()
+    for m, k in enumerate((0, 17, 130, 255)):
+        assert (y[m].to(torch.bfloat16) == What[:, k]).all()
+    assert (ybig[:, N:] == -7.0).all()
+
+
+def test_gemv_w4a16_cfg1_full_size():
+    cfg = inputs.CONFIGS[1]
+    l = cfg["layers"][0]
+    g, fmt = cfg["g"], cfg["fmt"]
+    Wt = inputs.layer_weights(l, DEV)
+    I = torch.rand(l["K"], device=DEV) * 100 + 1
+    tb, codes, scales, bits = quantise_on_gpu(Wt, I, g, g, fmt)
+    x = torch.randn((1, l["K"]), device=DEV).to(torch.bfloat16)
+    y = A.aaac_gemv_w4a16(x, codes, scales, bits, tb, g, g, fmt)
+    torch.cuda.synchronize()
+    # the oracle on a sample of rows (every 37th)
+    rows = np.arange(0, l["N"], 37)
+    ref, mag = oracle.gemv_w4a16(inputs.bits(x), host(codes)[rows], host(scales).view(np.uint16)[rows], None, u16(tb),
+                                 g, g, fmt)
+    err = np.abs(host(y)[:, rows].astype(np.float64) - ref)
+    assert (err <= gemv_tolerance(l["K"], mag) + np.spacing(np.abs(ref))).all()
+    # every output against the original layer: quantisation error only
+    exact = host(x.double() @ Wt.double().T)
+    assert np.abs(host(y) - exact).mean() < 0.2 * np.abs(exact).mean()
+
+
 # ------------------------------------------ benchmark settings, full size
 
 def test_config0_full():
