@@ -192,12 +192,12 @@ int aaac_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* se
  *   y[m, n] = sum_k x[m, k] * T_sigma[code[n, k]] * s[n, k / group_size]
  * computed from the codes, scales (and selection bits) as aaac_encode / aaac_encode_sel
  * write them; the dequantised weights are never stored and w^ is the real product (no
- * bf16 rounding of it).  Arithmetic: fp32 FMAs, every term exact; only the order of the
- * additions differs from exact evaluation: at most 22 + 4 * ceil(K / 2048) roundings lie
+ * bf16 rounding of it).  Arithmetic: fp32 accumulation of exact bf16 products, every term
+ * exact; only the order of the additions differs from exact evaluation: at most 22 + 4 * ceil(K / 2048) roundings lie
  * on the path of a term, so |error| <= (22 + 4 * ceil(K / 2048)) * 2^-24 * sum_k |x w^|
  * to first order.
- * Meant for a few rows of x (decode); x is taken four rows at a time, so larger M
- * re-reads the codes M/4 times.
+ * Meant for a few rows of x (decode); x is taken eight rows at a time, so larger M
+ * re-reads the codes M/8 times.
  *   x        dev bf16 [M x ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned
  *   codes    dev u8 [N x K/2] dense, 16-byte aligned; K % 32 == 0
  *   scales, sel_bits, sel_stride, tables_bf16, group_size, sel_size, fmt: as aaac_dequant_sel

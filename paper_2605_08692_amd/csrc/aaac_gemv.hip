@@ -6,17 +6,19 @@
 //
 // Mapping.  A lane owns 32 consecutive columns of a row (16 code bytes, one
 // 16-byte load), a wavefront a slab of 2048 columns; it keeps its slice of x in
-// registers as fp32 and walks down the rows of its block.  The 8 wavefronts of a
-// block take different slabs of the same rows (and different rows when the
-// matrix has fewer than 8 slabs).  Two codes are dequantised with one LDS read:
-// a 256-entry table per selection value maps a code byte to the pair
-// (T[low nibble], T[high nibble]) in fp32, replicated 16 times so that the 16
-// lanes served per clock never share a bank.  Within 16 columns the scale is
-// constant, so it multiplies the 16-term partial sum once.  Lane sums are reduced
-// over 16 lanes with DPP and added to the block's row sums in LDS; one fp32
-// store per output.  All arithmetic is fp32 (explicit FMAs); every term
-// x * T * s is exact in fp32, so only the order of the additions differs from an
-// exact evaluation.
+// registers as packed bf16 pairs, exactly as loaded, and walks down the rows of
+// its block, the loads of four rows in flight.  The 8 wavefronts of a block take different
+// slabs of the same rows (and different rows when the matrix has fewer than 8
+// slabs).  Two codes are dequantised with one LDS read: a 256-entry table per
+// selection value maps a code byte to the bf16 pair (T[low nibble], T[high
+// nibble]), replicated 32 times so that the 32 lanes served per clock never
+// share a bank, and one v_dot2c_f32_bf16 multiplies the pair with the two
+// activations and adds to the fp32 partial sum (bf16 products are exact in
+// fp32).  Within 16 columns the scale is constant, so it multiplies the partial
+// sum of those 16 columns once.  Lane sums are reduced over 16 lanes with DPP and
+// added to the block's row sums in LDS; one fp32 store per output.  Every term
+// x * T * s is exact in fp32, so only the order and number of the roundings in
+// the additions differ from an exact evaluation.
 #include "aaac_device.h"
 #include "aaac_internal.h"
 
@@ -27,20 +29,37 @@ namespace {
 constexpr int kGemvBlock = 512;
 constexpr int kGemvWaves = kGemvBlock / 64;
 constexpr int kSlabCols = 2048;     // columns of a wavefront: 64 lanes x 32 weights
-constexpr int kPairReplicas = 16;
+constexpr int kPairReplicas = 32;
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct alignas(16) GemvLds {
-  float2 pair[2][256][kPairReplicas];  // [sigma][code byte][replica] = (T[b & 15], T[b >> 4])
-  float y[kGemvMaxRows][4];            // row sums of the block
-  float T[32];
+  uint32_t pair[2][256][kPairReplicas];  // [sigma][code byte][replica] = bf16 T[b & 15] | bf16 T[b >> 4] << 16
+  float y[kGemvMaxRows][8];              // row sums of the block
+  uint32_t T[32];                        // the tables' bf16 bit patterns
 };
 
-// Unsigned scale value and the selection bit stored in its top bit.
+struct RowRegs {  // what a lane loads for one row: 16 code bytes, its scale code(s), selection bytes
+  uint4 c;
+  uint32_t sc, b0, b1;
+};
+
+// acc + a.lo * b.lo + a.hi * b.hi, a and b packed bf16 pairs
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  bf16x2 va, vb;
+  __builtin_memcpy(&va, &a, 4);
+  __builtin_memcpy(&vb, &b, 4);
+  return __builtin_amdgcn_fdot2_f32_bf16(va, vb, acc, false);
+}
+
+// Unsigned scale value and the selection bit stored in its top bit.  The E4M3 bits moved
+// into an fp32's exponent and mantissa fields read 2^-120 times the E4M3 value, subnormals
+// included (they land on fp32 subnormals); the product with 2^120 is exact.
 template <int FMT>
 __device__ __forceinline__ float scale_value(uint32_t code, uint32_t* sign) {
   if (FMT == 0) {
     *sign = code >> 7;
-    return e4m3_value(code & 0x7Fu);
+    return __uint_as_float((code & 0x7Fu) << 20) * 0x1p120f;
   }
   *sign = code >> 15;
   return __uint_as_float((code & 0x7FFFu) << 16);
@@ -54,14 +73,16 @@ __global__ __launch_bounds__(kGemvBlock) void gemv_w4a16_kernel(
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
     int64_t ldy, int rows_per_block) {
+  // rows whose loads go out together; fewer when x takes many registers, to keep two blocks per compute unit
+  constexpr int kRowsInFlight = MB >= 4 ? 2 : 4;
   __shared__ GemvLds sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
-  for (int i = tid; i < kGemvMaxRows * 4; i += kGemvBlock) (&sm.y[0][0])[i] = 0.0f;
+  if (tid < 32) sm.T[tid] = tables_bf16[tid];
+  for (int i = tid; i < kGemvMaxRows * 8; i += kGemvBlock) (&sm.y[0][0])[i] = 0.0f;
   __syncthreads();
   for (int i = tid; i < 2 * 256 * kPairReplicas; i += kGemvBlock) {
     const int b = (i / kPairReplicas) & 255, t = i / (256 * kPairReplicas);
-    (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
+    (&sm.pair[0][0][0])[i] = sm.T[16 * t + (b & 15)] | (sm.T[16 * t + (b >> 4)] << 16);
   }
   __syncthreads();
 
@@ -79,17 +100,15 @@ __global__ __launch_bounds__(kGemvBlock) void gemv_w4a16_kernel(
     for (int slab = wave % slabs_at_once; slab < slabs; slab += slabs_at_once) {
       const int k0 = slab * kSlabCols + lane * 32;
       const bool active = k0 < K;
-      // this lane's slice of x, rows beyond M are zero
-      float xr[MB][32];
+      // this lane's slice of x as 16 bf16 pairs per row; rows beyond M are zero
+      uint32_t xp[MB][16];
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           uint4 v = make_uint4(0, 0, 0, 0);
           if (active && m < M) v = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k0 + 8 * q);
-          const W8 w = unpack8(v);
-#pragma unroll
-          for (int p = 0; p < 8; ++p) xr[m][8 * q + p] = w.w[p];
+          xp[m][4 * q] = v.x; xp[m][4 * q + 1] = v.y; xp[m][4 * q + 2] = v.z; xp[m][4 * q + 3] = v.w;
         }
       }
       const uint8_t* cbase = codes + (active ? k0 / 2 : 0);
@@ -97,70 +116,88 @@ __global__ __launch_bounds__(kGemvBlock) void gemv_w4a16_kernel(
       const int jsel = active ? k0 >> sshift : 0;   // selection group of the lane's first column
       const int jsel_hi = active ? (k0 + 16) >> sshift : 0;
 
-      uint4 c_next = make_uint4(0, 0, 0, 0);
-      uint32_t s_next = 0, b_next = 0;
-      auto fetch = [&](int row) {
-        c_next = *reinterpret_cast<const uint4*>(cbase + (int64_t)row * row_bytes);
-        const int64_t g = (int64_t)row * Gs + sidx;
-        if (FMT == 0) {
-          if (G16) s_next = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g);
-          else s_next = static_cast<const uint8_t*>(scales)[g];
-        } else {
-          if (G16) s_next = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g);
-          else s_next = static_cast<const uint16_t*>(scales)[g];
-        }
-        if (sel_bits != nullptr) {
-          const uint8_t* sb = sel_bits + (int64_t)row * sel_stride;
-          b_next = ((uint32_t)(sb[jsel >> 3] >> (jsel & 7)) & 1u) | (((uint32_t)(sb[jsel_hi >> 3] >> (jsel_hi & 7)) & 1u) << 1);
-        }
-      };
-      int row = r0 + row_first;
-      if (active && row < r1) fetch(row);
-      for (; row < r1; row += row_step) {
-        const uint4 c = c_next;
-        const uint32_t sc = s_next, bits = b_next;
-        if (active && row + row_step < r1) fetch(row + row_step);
-        // the two 16-column halves of the lane: scale value and selection
-        float s_val[2];
-        uint32_t sigma[2];
-        if (G16) {
-          const uint32_t width = FMT == 0 ? 8u : 16u, mask = FMT == 0 ? 0xFFu : 0xFFFFu;
-          s_val[0] = scale_value<FMT>(sc & mask, &sigma[0]);
-          s_val[1] = scale_value<FMT>((sc >> width) & mask, &sigma[1]);
-        } else {
-          s_val[0] = s_val[1] = scale_value<FMT>(sc, &sigma[0]);
-          sigma[1] = sigma[0];
-        }
-        if (sel_bits != nullptr) { sigma[0] = bits & 1u; sigma[1] = bits >> 1; }
-        if (!active) s_val[0] = s_val[1] = 0.0f;
-        const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-        float total[MB];
+      // Rows are taken four at a time: their loads go out together, then they are worked on in
+      // order.  (Keeping a second set of four in flight did not pay: the kernel is bound by its
+      // vector instructions, and the extra registers cost occupancy.)
+      auto fetch = [&](RowRegs (&rr)[kRowsInFlight], int base) {
 #pragma unroll
-        for (int m = 0; m < MB; ++m) total[m] = 0.0f;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const float2* tab = &sm.pair[sigma[h]][0][rep];
-          float part[MB];
-#pragma unroll
-          for (int m = 0; m < MB; ++m) part[m] = 0.0f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const uint32_t byte = (cw[2 * h + i / 4] >> (8 * (i % 4))) & 0xFFu;
-            const float2 t = tab[byte * kPairReplicas];
-#pragma unroll
-            for (int m = 0; m < MB; ++m) {
-              part[m] = __builtin_fmaf(xr[m][16 * h + 2 * i], t.x, part[m]);
-              part[m] = __builtin_fmaf(xr[m][16 * h + 2 * i + 1], t.y, part[m]);
+        for (int u = 0; u < kRowsInFlight; ++u) {
+          const int row = base + u * row_step;
+          rr[u].c = make_uint4(0, 0, 0, 0);
+          rr[u].sc = 0;
+          rr[u].b0 = 0;
+          rr[u].b1 = 0;
+          if (active && row < r1) {
+            rr[u].c = *reinterpret_cast<const uint4*>(cbase + (int64_t)row * row_bytes);
+            const int64_t g = (int64_t)row * Gs + sidx;
+            if (FMT == 0) {
+              if (G16) rr[u].sc = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g);
+              else rr[u].sc = static_cast<const uint8_t*>(scales)[g];
+            } else {
+              if (G16) rr[u].sc = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g);
+              else rr[u].sc = static_cast<const uint16_t*>(scales)[g];
+            }
+            if (sel_bits != nullptr) {  // the bytes only; the bits are picked out when the row is worked on
+              const uint8_t* sb = sel_bits + (int64_t)row * sel_stride;
+              rr[u].b0 = sb[jsel >> 3];
+              rr[u].b1 = sb[jsel_hi >> 3];
             }
           }
-#pragma unroll
-          for (int m = 0; m < MB; ++m) total[m] = __builtin_fmaf(part[m], s_val[h], total[m]);
         }
+      };
+      auto work = [&](const RowRegs (&rr)[kRowsInFlight], int base) {
 #pragma unroll
-        for (int m = 0; m < MB; ++m) {
-          const float v = group_sum<16>(total[m]);
-          if ((lane & 15) == 0) atomicAdd(&sm.y[row - r0][m], v);
+        for (int u = 0; u < kRowsInFlight; ++u) {
+          const int row = base + u * row_step;
+          if (row < r1) {
+            // the two 16-column halves of the lane: scale value and selection
+            float s_val[2];
+            uint32_t sigma[2];
+            if (G16) {
+              const uint32_t width = FMT == 0 ? 8u : 16u, mask = FMT == 0 ? 0xFFu : 0xFFFFu;
+              s_val[0] = scale_value<FMT>(rr[u].sc & mask, &sigma[0]);
+              s_val[1] = scale_value<FMT>((rr[u].sc >> width) & mask, &sigma[1]);
+            } else {
+              s_val[0] = s_val[1] = scale_value<FMT>(rr[u].sc, &sigma[0]);
+              sigma[1] = sigma[0];
+            }
+            if (sel_bits != nullptr) {
+              sigma[0] = (rr[u].b0 >> (jsel & 7)) & 1u;
+              sigma[1] = (rr[u].b1 >> (jsel_hi & 7)) & 1u;
+            }
+            if (!active) s_val[0] = s_val[1] = 0.0f;
+            const uint32_t cw[4] = {rr[u].c.x, rr[u].c.y, rr[u].c.z, rr[u].c.w};
+            float total[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) total[m] = 0.0f;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const uint32_t* tab = &sm.pair[sigma[h]][0][rep];
+              float part[MB];
+#pragma unroll
+              for (int m = 0; m < MB; ++m) part[m] = 0.0f;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                const uint32_t byte = (cw[2 * h + i / 4] >> (8 * (i % 4))) & 0xFFu;
+                const uint32_t t = tab[byte * kPairReplicas];
+#pragma unroll
+                for (int m = 0; m < MB; ++m) part[m] = dot2_bf16(xp[m][8 * h + i], t, part[m]);
+              }
+#pragma unroll
+              for (int m = 0; m < MB; ++m) total[m] = __builtin_fmaf(part[m], s_val[h], total[m]);
+            }
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+              const float v = group_sum<16>(total[m]);
+              if ((lane & 15) == 0) atomicAdd(&sm.y[row - r0][m], v);
+            }
+          }
         }
+      };
+      RowRegs rr[kRowsInFlight];
+      for (int base = r0 + row_first; base < r1; base += kRowsInFlight * row_step) {
+        fetch(rr, base);
+        work(rr, base);
       }
     }
   }
@@ -177,7 +214,11 @@ hipError_t launch_mb(int mb, dim3 grid, hipStream_t stream, const uint16_t* x, i
                      const uint8_t* codes, const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
                      const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
                      int rows_per_block) {
-  if (mb == 1)
+  if (mb == 8)
+    gemv_w4a16_kernel<FMT, G16, 8><<<grid, kGemvBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
+                                                                   tables_bf16, N, K, gshift, sshift, y, ldy,
+                                                                   rows_per_block);
+  else if (mb == 1)
     gemv_w4a16_kernel<FMT, G16, 1><<<grid, kGemvBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
                                                                    tables_bf16, N, K, gshift, sshift, y, ldy,
                                                                    rows_per_block);
@@ -224,9 +265,9 @@ hipError_t launch_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   const dim3 grid((unsigned)((N + rpb - 1) / rpb));
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
-  for (int64_t m0 = 0; m0 < M; m0 += 4) {  // four rows of x at a time
-    const int rows = (int)(M - m0 < 4 ? M - m0 : 4);
-    const int mb = rows == 1 ? 1 : rows == 2 ? 2 : 4;
+  for (int64_t m0 = 0; m0 < M; m0 += 8) {  // eight rows of x at a time
+    const int rows = (int)(M - m0 < 8 ? M - m0 : 8);
+    const int mb = rows == 1 ? 1 : rows == 2 ? 2 : rows <= 4 ? 4 : 8;
     hipError_t e;
 #define AAAC_GEMV(FMT, G16)                                                                                  \
   e = launch_mb<FMT, G16>(mb, grid, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride,       \
