@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--quantile-init", action="store_true",
                     help="start from the quantile tables of Alg. 1 (computed on the GPU inside the fit) instead of "
                          "the format grid; the fit then goes through aaac_fit_nested")
+    ap.add_argument("--gemv-rows", type=int, default=0,
+                    help="after the timed steps, also time aaac_gemv_w4a16 (the quantised layers applied to this many "
+                         "rows of activations) and report it as gemv_w4a16")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -206,6 +209,38 @@ def main():
         iter_us = assign_ms * 1e3 / n_outer
         weights_per_s_iter = n_w / (iter_us * 1e-6)
 
+    gemv = None
+    if args.gemv_rows > 0:
+        # the quantised layers of the last step applied to a few activation rows; 20 calls per layer
+        # are captured in a HIP graph so that the host's call overhead does not hide the kernel
+        Mx = args.gemv_rows
+        xs = {L["name"]: torch.randn((Mx, L["K"]), device=dev).to(torch.bfloat16) for L in layers}
+        ys = {L["name"]: torch.empty((Mx, L["N"]), dtype=torch.float32, device=dev) for L in layers}
+        side = torch.cuda.Stream()
+        per_layer = []
+        for L in layers:
+            call = lambda st: A.aaac_gemv_w4a16(xs[L["name"]], L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt,
+                                                y=ys[L["name"]], stream=st)
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                call(side)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    for _ in range(20):
+                        call(side)
+                graph.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(side)
+                graph.replay()
+                e1.record(side)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            nbytes = L["N"] * L["K"] * (0.5 + (1 if fmt == A.NVFP4 else 2) / g + (1 / (8 * S) if S < g else 0))
+            per_layer.append({"layer": L["name"], "us": us, "weights_per_s": L["N"] * L["K"] / (us * 1e-6),
+                              "hbm_GBs": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS})
+        gemv = {"rows_of_x": Mx, "bound": "hbm", "peak_GBs": HBM_PEAK_GBS, "layers": per_layer}
+
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -250,6 +285,8 @@ def main():
 
     if refine is not None:
         out["refine_roofline"] = refine
+    if gemv is not None:
+        out["gemv_w4a16"] = gemv
     if quant is not None:
         out["quantile_init"] = quant
         out["config"]["init"] = "quantile"

@@ -165,8 +165,9 @@ struct alignas(16) EncodeLds {
 // first lane of a scale group stores the scale; the table choice goes into the
 // scale's top bit when both groups coincide (sel_bits null), otherwise into the
 // separate bit array: selection group j of a row is bit j % 8 of byte j / 8.
-// LANES: lanes per selection group; scale_lanes: lanes per scale group.
-template <int LANES, int FMT>
+// LANES: lanes per selection group; scale_lanes: lanes per scale group; SAME: the two groups
+// coincide (scale_lanes == LANES, no separate bits).
+template <int LANES, int FMT, bool SAME>
 __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     const uint16_t* __restrict__ W, int N, int K, int64_t ldw, const float* __restrict__ importance,
     const uint16_t* __restrict__ tables_bf16, uint8_t* __restrict__ codes, void* __restrict__ scales,
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
   constexpr int kSelBytes = LANES <= 8 ? 8 / LANES : 1;
   const int sel_lane = lane & (kSelBytes - 1);
   const int sel_byte = strip * kSelBytes + sel_lane;             // byte index inside the row
-  const bool sel_writer = sel_bits != nullptr && has_strip && lane < kSelBytes &&
+  const bool sel_writer = !SAME && sel_bits != nullptr && has_strip && lane < kSelBytes &&
                           (int64_t)sel_byte * 64 * LANES < K;   // the byte's first group starts inside the row
   const uint16_t* wbase = W + (active ? col : 0);
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     row = next;
     const W8 x = unpack8(v);
     float s;
-    const uint32_t sc = scale_code<FMT>(group_max_lanes(absmax8(x), scale_lanes), &s);
+    const uint32_t sc = scale_code<FMT>(SAME ? group_max<LANES>(absmax8(x)) : group_max_lanes(absmax8(x), scale_lanes), &s);
     const float r = div_rn(1.0f, s);
     Lane8 a;
     assign_fast(x, r, Iv, sm.st, sm.sl, inv, off, rep4, a);
@@ -241,9 +242,9 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
     }
     if (active) {
       *reinterpret_cast<uint32_t*>(codes + ((int64_t)cur * K + col) / 2) = packed;
-      if ((lane % scale_lanes) == 0) {
-        const int64_t g = (int64_t)cur * Gs + col / (8 * scale_lanes);
-        const bool sign = sel_bits == nullptr && sigma;
+      if ((lane % (SAME ? LANES : scale_lanes)) == 0) {
+        const int64_t g = (int64_t)cur * Gs + col / (8 * (SAME ? LANES : scale_lanes));
+        const bool sign = (SAME || sel_bits == nullptr) && sigma;
         if (FMT == 0) static_cast<uint8_t*>(scales)[g] = (uint8_t)(sc | (sign ? 0x80u : 0u));
         else static_cast<uint16_t*>(scales)[g] = (uint16_t)(sc | (sign ? 0x8000u : 0u));
       }
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
 
 // sel_bits null: the table choice is the top bit of the scale; otherwise bit j % 8 of byte
 // j / 8 of the row's sel_stride bytes, j = column / sel_size.
-template <int FMT>
+template <int FMT, bool BITS>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(
     const uint8_t* __restrict__ codes, const void* __restrict__ scales,
     const uint8_t* __restrict__ sel_bits, int64_t sel_stride, int sel_size,
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void dequant_kernel(
     sigma = sc >> 15;
     s = __uint_as_float((sc & 0x7FFFu) << 16);
   }
-  if (sel_bits != nullptr) {
+  if (BITS) {
     const int64_t j = col / sel_size;
     sigma = (sel_bits[row * sel_stride + (j >> 3)] >> (j & 7)) & 1u;
   }
@@ -400,14 +401,17 @@ struct EncodeCall {
 template <int LANES>
 static hipError_t launch_encode_lanes(const EncodeCall& c, hipStream_t stream) {
   const FitPlan p = make_fit_plan(c.N, c.K, c.ldw, c.group_size, 8 * LANES);
-  if (c.fmt == 0)
-    encode_kernel<LANES, 0><<<p.blocks, kSearchBlock, 0, stream>>>(
-        c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride,
-        c.group_size / 8, p.strips, p.strips_per_block, p.strip_groups, p.rows_per_block);
-  else
-    encode_kernel<LANES, 1><<<p.blocks, kSearchBlock, 0, stream>>>(
-        c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride,
-        c.group_size / 8, p.strips, p.strips_per_block, p.strip_groups, p.rows_per_block);
+#define AAAC_ENCODE(FMT, SAME)                                                                              \
+  encode_kernel<LANES, FMT, SAME><<<p.blocks, kSearchBlock, 0, stream>>>(                                    \
+      c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride, \
+      c.group_size / 8, p.strips, p.strips_per_block, p.strip_groups, p.rows_per_block)
+  const bool same = c.group_size == 8 * LANES;
+  if (c.fmt == 0) {
+    if (same) AAAC_ENCODE(0, true); else AAAC_ENCODE(0, false);
+  } else {
+    if (same) AAAC_ENCODE(1, true); else AAAC_ENCODE(1, false);
+  }
+#undef AAAC_ENCODE
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }
@@ -434,12 +438,15 @@ hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_
   const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
   uint16_t* out = static_cast<uint16_t*>(W_hat);
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
-  if (fmt == 0)
-    dequant_kernel<0><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, N, K,
-                                                      group_size, out, ldo);
-  else
-    dequant_kernel<1><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, N, K,
-                                                      group_size, out, ldo);
+#define AAAC_DEQUANT(FMT, BITS)                                                                              \
+  dequant_kernel<FMT, BITS><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, \
+                                                            N, K, group_size, out, ldo)
+  if (fmt == 0) {
+    if (bits) AAAC_DEQUANT(0, true); else AAAC_DEQUANT(0, false);
+  } else {
+    if (bits) AAAC_DEQUANT(1, true); else AAAC_DEQUANT(1, false);
+  }
+#undef AAAC_DEQUANT
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }
