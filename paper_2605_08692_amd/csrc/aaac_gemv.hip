@@ -100,7 +100,8 @@ __global__ __launch_bounds__(kGemvBlock) void gemv_w4a16_kernel(
     for (int slab = wave % slabs_at_once; slab < slabs; slab += slabs_at_once) {
       const int k0 = slab * kSlabCols + lane * 32;
       const bool active = k0 < K;
-      // this lane's slice of x as 16 bf16 pairs per row; rows beyond M are zero
+      // this lane's slice of x as 16 bf16 pairs per row; rows beyond M are zero, and so is the slice of
+      // a lane past the last column (its codes and scales read as zero too: it adds 0 * 0)
       uint32_t xp[MB][16];
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
@@ -165,7 +166,6 @@ __global__ __launch_bounds__(kGemvBlock) void gemv_w4a16_kernel(
               sigma[0] = (rr[u].b0 >> (jsel & 7)) & 1u;
               sigma[1] = (rr[u].b1 >> (jsel_hi & 7)) & 1u;
             }
-            if (!active) s_val[0] = s_val[1] = 0.0f;
             const uint32_t cw[4] = {rr[u].c.x, rr[u].c.y, rr[u].c.z, rr[u].c.w};
             float total[MB];
 #pragma unroll
