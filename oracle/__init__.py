@@ -72,6 +72,8 @@ def lib():
         L.oracle_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P]
         L.oracle_gemv_w4a16.restype = _INT
         L.oracle_gemv_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _P]
+        L.oracle_gemm_w4a16.restype = _INT
+        L.oracle_gemm_w4a16.argtypes = L.oracle_gemv_w4a16.argtypes
         L.oracle_encode.restype = _INT
         L.oracle_encode.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _P, _P]
         L.oracle_dequant.restype = _INT
@@ -297,9 +299,9 @@ def quantile_init(W_bits, g, fmt):
     return grid
 
 
-def gemv_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt):
+def gemv_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt, round_weights=False):
     """y = x W^^T with the quantised layer: x_bits uint16 [M, K] (bf16) -> (y float32 [M, N],
-    abs_sum float64 [M, N] = sum_k |x * w^|)."""
+    abs_sum float64 [M, N] = sum_k |x * w^|).  round_weights: w^ rounded to bf16 first."""
     x = _c(x_bits, np.uint16)
     M, K = x.shape
     codes = _c(codes, np.uint8)
@@ -310,7 +312,12 @@ def gemv_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt):
     bits = None if sel_bits is None else _c(sel_bits, np.uint8)
     y = np.empty((M, N), np.float32)
     mag = np.empty((M, N), np.float64)
-    _check(lib().oracle_gemv_w4a16(_ptr(x), M, K, _ptr(codes), _ptr(scales), _ptr(bits),
-                                   0 if bits is None else bits.shape[1], _ptr(tb), N, K, g, S, fmt,
-                                   _ptr(y), _ptr(mag)), "gemv_w4a16")
+    fn = lib().oracle_gemm_w4a16 if round_weights else lib().oracle_gemv_w4a16
+    _check(fn(_ptr(x), M, K, _ptr(codes), _ptr(scales), _ptr(bits),
+              0 if bits is None else bits.shape[1], _ptr(tb), N, K, g, S, fmt, _ptr(y), _ptr(mag)), "gemv_w4a16")
     return y, mag
+
+
+def gemm_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt):
+    """The product with the dequantised weights rounded to bf16 (those dequant_sel returns)."""
+    return gemv_w4a16(x_bits, codes, scales, sel_bits, tables_bf16, g, S, fmt, round_weights=True)

@@ -606,9 +606,10 @@ int oracle_quantile_init(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, i
 // abs_sum (optional, [M x N]) receives sum_k |x * w^|, the quantity a
 // floating-point summation error bound is stated against.
 // sel_bits / S as in oracle_dequant_sel.
-int oracle_gemv_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
-                      const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
-                      int64_t N, int64_t K, int g, int S, int fmt, float* y, double* abs_sum) {
+static int w4a16_product(bool round_weights, const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* codes,
+                         const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
+                         const uint16_t* tables_bf16, int64_t N, int64_t K, int g, int S, int fmt, float* y,
+                         double* abs_sum) {
   if (!valid_shape(N, K, K, g) || !valid_shape(N, K, K, S) || S > g || M < 0 || ldx < K) return -1;
   if (S < g && !sel_bits) return -1;
   int64_t G = K / g;
@@ -634,8 +635,9 @@ int oracle_gemv_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* 
         }
         uint8_t byte = codes[(n * K + k) / 2];
         int code = (k & 1) ? (byte >> 4) : (byte & 15);
-        long double t = static_cast<long double>(bf16_to_f32(tables_bf16[16 * sigma + code])) *
-                        static_cast<long double>(s) * static_cast<long double>(bf16_to_f32(x[m * ldx + k]));
+        float w = bf16_to_f32(tables_bf16[16 * sigma + code]) * s;  // exact: 8 x 8 significant bits
+        if (round_weights) w = bf16_to_f32(f32_to_bf16(w));
+        long double t = static_cast<long double>(w) * static_cast<long double>(bf16_to_f32(x[m * ldx + k]));
         acc.add(t);
         mag.add(std::fabs(t));
       }
@@ -643,6 +645,23 @@ int oracle_gemv_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* 
       if (abs_sum) abs_sum[m * N + n] = static_cast<double>(mag.value());
     }
   return 0;
+}
+
+int oracle_gemv_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                      const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                      int64_t N, int64_t K, int g, int S, int fmt, float* y, double* abs_sum) {
+  return w4a16_product(false, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, g, S, fmt, y,
+                       abs_sum);
+}
+
+// The same product with the dequantised weights rounded to bf16 first, w^ =
+// bf16(T_sigma[code] * s), i.e. exactly the weights oracle_dequant_sel returns:
+// what a matrix-core kernel with bf16 operands computes.
+int oracle_gemm_w4a16(const uint16_t* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                      const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                      int64_t N, int64_t K, int g, int S, int fmt, float* y, double* abs_sum) {
+  return w4a16_product(true, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, g, S, fmt, y,
+                       abs_sum);
 }
 
 }  // extern "C"

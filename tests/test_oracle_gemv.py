@@ -99,3 +99,20 @@ def test_linear_in_x_and_rejects_bad_shapes():
     assert np.allclose(yab, ya.astype(np.float64) + yb, rtol=1e-6, atol=1e-7)
     with pytest.raises(ValueError):
         oracle.gemv_w4a16(a, codes, scales, None, tb, 128, 16, fmt)   # S < g without selection bits
+
+
+@pytest.mark.parametrize("g,S,fmt", [(16, 16, oracle.NVFP4), (128, 16, oracle.INT4)])
+def test_rounded_weight_product_is_the_matmul_with_the_dequantised_layer(g, S, fmt):
+    # oracle.gemm_w4a16 = x times exactly the bf16 weights that the pinned dequantisation returns
+    N, K, M = 10, 256, 3
+    _, tb, codes, scales, bits = quantised_layer(101 + g, N, K, g, S, fmt)
+    rng = np.random.default_rng(g + 1)
+    x = bf16_bits(rng.standard_normal((M, K)))
+    y, mag = oracle.gemm_w4a16(x, codes, scales, bits, tb, g, S, fmt)
+    What = bf16_vals(oracle.dequant_sel(codes, scales, bits, tb, g, S, fmt)).astype(np.float64)
+    xr = bf16_vals(x).astype(np.float64)
+    assert np.allclose(y, xr @ What.T, rtol=1e-6, atol=1e-6 * np.abs(xr @ What.T).max())
+    assert np.allclose(mag, (np.abs(xr)[:, None, :] * np.abs(What)[None, :, :]).sum(axis=2), rtol=1e-12)
+    # it differs from the unrounded product by at most the bf16 rounding of each weight
+    y0, mag0 = oracle.gemv_w4a16(x, codes, scales, bits, tb, g, S, fmt)
+    assert (np.abs(y.astype(np.float64) - y0) <= 2.0 ** -8 * mag0).all() and (y != y0).any()
