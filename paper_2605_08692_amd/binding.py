@@ -68,6 +68,8 @@ def library():
         L.aaac_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _SZ, _P]
         L.aaac_gemv_w4a16.restype = _INT
         L.aaac_gemv_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64, _P]
+        L.aaac_gemm_w4a16.restype = _INT
+        L.aaac_gemm_w4a16.argtypes = L.aaac_gemv_w4a16.argtypes
         L.aaac_encode_sel.restype = _INT
         L.aaac_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64, _P]
         L.aaac_dequant_sel.restype = _INT
@@ -281,7 +283,14 @@ def aaac_quantile_init(W, group_size, fmt, grid=None, ws=None, stream=None):
     return grid
 
 
-def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None):
+def aaac_gemm_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None):
+    """x bf16 [M, K] times the quantised layer on the matrix cores (weights rounded to bf16) -> y fp32 [M, N]."""
+    return aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y, stream,
+                           _entry="aaac_gemm_w4a16")
+
+
+def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None,
+                    _entry="aaac_gemv_w4a16"):
     """x bf16 [M, K] times the quantised layer -> y fp32 [M, N]."""
     assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
     M, K = x.shape
@@ -291,7 +300,7 @@ def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_siz
     ldx = x.stride(0) if M > 1 else max(x.stride(0), K)
     ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
     stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
-    _check(library().aaac_gemv_w4a16(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
-                                     _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy,
-                                     _stream(stream)), "aaac_gemv_w4a16")
+    _check(getattr(library(), _entry)(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
+                                      _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy,
+                                      _stream(stream)), _entry)
     return y

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaaac.so")
-SOURCES = ["aaac_api.hip", "aaac_kernels.hip", "aaac_lloyd.hip", "aaac_quantile.hip", "aaac_gemv.hip"]
+SOURCES = ["aaac_api.hip", "aaac_kernels.hip", "aaac_lloyd.hip", "aaac_quantile.hip", "aaac_gemv.hip", "aaac_gemm.hip"]
 
 # -ffp-contract=off: every fp32 operation that decides a code or a selection bit
 # must stay a single IEEE operation.  Packed fp32 instructions are switched off.

@@ -53,6 +53,34 @@ int check_layer(const aaac_layer_t& l, int group_size) {
   return check_matrix(l.W, l.N, l.K, l.ldw, group_size);
 }
 
+// Shared body of the two W4A16 products: vector ALUs (a few rows of x, weights unrounded) or matrix
+// cores (weights rounded to bf16).
+int w4a16_entry(bool matrix_cores, const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
+                const void* scales, const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                int64_t N, int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
+                void* hip_stream) {
+  if (tables_bf16 == nullptr) return AAAC_ERR_NULL;
+  if (M > 0 && N > 0 && (y == nullptr || (K > 0 && (x == nullptr || codes == nullptr || scales == nullptr))))
+    return AAAC_ERR_NULL;
+  if (M < 0 || N < 0 || K < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31)
+    return AAAC_ERR_SHAPE;
+  if (!valid_group(group_size) || !valid_sel(sel_size, group_size)) return AAAC_ERR_SHAPE;
+  if (K % group_size != 0 || K % (matrix_cores ? 64 : 32) != 0) return AAAC_ERR_SHAPE;
+  if (ldx < K || ldx % 8 != 0 || ldy < N) return AAAC_ERR_SHAPE;
+  if (sel_size < group_size) {
+    if (M > 0 && N > 0 && K > 0 && sel_bits == nullptr) return AAAC_ERR_NULL;
+    if (sel_stride < (K / sel_size + 7) / 8) return AAAC_ERR_SHAPE;
+  }
+  if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(codes, 16) || !aligned(scales, matrix_cores ? 8 : 4) || !aligned(y, 4))
+    return AAAC_ERR_SHAPE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  return from_hip(matrix_cores ? aaac::launch_gemm_w4a16(x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16,
+                                                         N, K, group_size, sel_size, fmt, y, ldy, stream)
+                               : aaac::launch_gemv_w4a16(x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16,
+                                                         N, K, group_size, sel_size, fmt, y, ldy, stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -250,23 +278,16 @@ int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
                     const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
                     int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
                     void* hip_stream) {
-  if (tables_bf16 == nullptr) return AAAC_ERR_NULL;
-  if (M > 0 && N > 0 && (y == nullptr || (K > 0 && (x == nullptr || codes == nullptr || scales == nullptr))))
-    return AAAC_ERR_NULL;
-  if (M < 0 || N < 0 || K < 0 || M >= (int64_t)1 << 31 || N >= (int64_t)1 << 31 || K >= (int64_t)1 << 31)
-    return AAAC_ERR_SHAPE;
-  if (!valid_group(group_size) || !valid_sel(sel_size, group_size)) return AAAC_ERR_SHAPE;
-  if (K % group_size != 0 || K % 32 != 0) return AAAC_ERR_SHAPE;
-  if (ldx < K || ldx % 8 != 0 || ldy < N) return AAAC_ERR_SHAPE;
-  if (sel_size < group_size) {
-    if (M > 0 && N > 0 && K > 0 && sel_bits == nullptr) return AAAC_ERR_NULL;
-    if (sel_stride < (K / sel_size + 7) / 8) return AAAC_ERR_SHAPE;
-  }
-  if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
-  if (!aligned(x, 16) || !aligned(codes, 16) || !aligned(scales, 4) || !aligned(y, 4)) return AAAC_ERR_SHAPE;
-  return from_hip(aaac::launch_gemv_w4a16(x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
-                                          group_size, sel_size, fmt, y, ldy,
-                                          static_cast<hipStream_t>(hip_stream)));
+  return w4a16_entry(false, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, group_size, sel_size,
+                     fmt, y, ldy, hip_stream);
+}
+
+int aaac_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                    const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
+                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
+                    void* hip_stream) {
+  return w4a16_entry(true, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, group_size, sel_size,
+                     fmt, y, ldy, hip_stream);
 }
 
 }  // extern "C"

@@ -1,0 +1,244 @@
+// The quantised layer applied to a batch of activation rows on the matrix cores
+// (W4A16): y[m, n] = sum_k x[m, k] * w^[n, k] with w^ = bf16(T_sigma[code] * s), the
+// weights of paper Eq. "aaac_dequant" rounded to bf16 as aaac_dequant stores them,
+// fp32 accumulation (v_mfma_f32_16x16x32_bf16).  The codes are dequantised in
+// registers straight into the MFMA's A operand; the dequantised weights never go
+// to memory.
+//
+// Mapping.  D[n][m] = sum_k A[n][k] B[k][m] with A = w^ (16 rows of the layer) and
+// B = x^T (16 rows of x).  In a 16x16x32 MFMA lane (r, q), r = lane % 16, q = lane / 16,
+// supplies A[r][8q..8q+7] and B[8q..8q+7][r] and receives D[4q..4q+3][r].  The sum
+// over k may run in any order as long as A and B agree, so per 256-column chunk a lane
+// takes the 64 consecutive columns 64q..64q+63 of its row (two 16-byte code loads: the
+// four lanes of a row read one 128-byte line) and feeds them in eight steps of 8;
+// the lane that holds x row r takes the same columns of x.  A block of 8 wavefronts is
+// NS row tiles x 8/NS slices of the chunks (NS chosen by the host: many rows -> 8 tiles
+// that read the same x at the same time and share it in the L1 cache; few rows ->
+// more slices of K), reduced through a tile in LDS.
+//
+// Two codes are dequantised with one LDS read (code byte -> fp32 pair of table
+// values), multiplied by the scale (exact: 8 x 8 significant bits) and rounded to
+// bf16 pairs by the hardware conversion.
+#include "aaac_device.h"
+#include "aaac_internal.h"
+
+namespace aaac {
+
+namespace {
+
+constexpr int kGemmBlock = 512;
+constexpr int kGemmWaves = kGemmBlock / 64;
+constexpr int kChunkCols = 256;      // columns per wavefront step: 4 lane quarters x 64
+constexpr int kGemmReplicas = 8;     // copies of the pair table
+constexpr int kTilePad = 1;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int MT>
+struct alignas(16) GemmLds {
+  float2 pair[2][256][kGemmReplicas];              // [sigma][code byte][replica] = (T[b & 15], T[b >> 4])
+  float y[kGemmWaves * 16][MT * 16 + kTilePad];    // the block's output tile
+  float T[32];
+};
+
+template <int FMT>
+__device__ __forceinline__ float gemm_scale_value(uint32_t code, uint32_t* sign) {
+  if (FMT == 0) {
+    *sign = code >> 7;
+    return __uint_as_float((code & 0x7Fu) << 20) * 0x1p120f;  // E4M3 -> fp32, subnormals included
+  }
+  *sign = code >> 15;
+  return __uint_as_float((code & 0x7FFFu) << 16);
+}
+
+// two fp32 -> packed bf16 pair, round to nearest even
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);
+  uint32_t u;
+  __builtin_memcpy(&u, &b, 4);
+  return u;
+}
+
+// MT: tiles of 16 rows of x held at once (M <= 16 * MT in this launch); NS: row tiles per block.
+template <int FMT, int MT>
+__global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int M, const uint8_t* __restrict__ codes,
+    const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
+    const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
+    int64_t ldy, int NS) {
+  __shared__ GemmLds<MT> sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
+  for (int i = tid; i < kGemmWaves * 16 * (MT * 16 + kTilePad); i += kGemmBlock) (&sm.y[0][0])[i] = 0.0f;
+  __syncthreads();
+  for (int i = tid; i < 2 * 256 * kGemmReplicas; i += kGemmBlock) {
+    const int b = (i / kGemmReplicas) & 255, t = i / (256 * kGemmReplicas);
+    (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
+  }
+  __syncthreads();
+
+  const int r = lane & 15, q = lane >> 4;
+  const int KS = kGemmWaves / NS;            // slices of the chunk sequence
+  const int sub = wave % NS, slice = wave / NS;
+  const int n_base = blockIdx.x * 16 * NS;
+  const int n = n_base + sub * 16 + r;       // the layer row this lane dequantises
+  const bool has_row = n < N;
+  const int Gs = K >> gshift;
+  const int rep = lane & (kGemmReplicas - 1);
+  const int64_t row_bytes = K / 2;
+  const int chunks = (K + kChunkCols - 1) / kChunkCols;
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int j = 0; j < MT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int c = slice; c < chunks; c += KS) {
+    const int k0 = c * kChunkCols + 64 * q;  // this lane's 64 columns
+    const bool in_k = k0 < K;                // K % 64 == 0: all 64 or none
+    uint4 cw4[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+    uint32_t sc[4] = {0, 0, 0, 0};           // scale code of each 16-column block
+    uint32_t selbyte = 0;
+    if (in_k && has_row) {
+      const uint8_t* cp = codes + (int64_t)n * row_bytes + k0 / 2;
+      cw4[0] = *reinterpret_cast<const uint4*>(cp);
+      cw4[1] = *reinterpret_cast<const uint4*>(cp + 16);
+      const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
+      if (gshift == 4) {  // four scale groups in the lane's 64 columns
+        if (FMT == 0) {
+          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(scales) + g0);
+          sc[0] = v & 0xFFu; sc[1] = (v >> 8) & 0xFFu; sc[2] = (v >> 16) & 0xFFu; sc[3] = v >> 24;
+        } else {
+          const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(scales) + g0);
+          sc[0] = v.x & 0xFFFFu; sc[1] = v.x >> 16; sc[2] = v.y & 0xFFFFu; sc[3] = v.y >> 16;
+        }
+      } else if (gshift == 5) {  // two
+        if (FMT == 0) {
+          const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
+          sc[0] = sc[1] = v & 0xFFu; sc[2] = sc[3] = v >> 8;
+        } else {
+          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
+          sc[0] = sc[1] = v & 0xFFFFu; sc[2] = sc[3] = v >> 16;
+        }
+      } else {  // one
+        const uint32_t v = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
+                                    : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
+        sc[0] = sc[1] = sc[2] = sc[3] = v;
+      }
+      if (sel_bits != nullptr) selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
+    }
+    float s_val[4];
+    uint32_t sigma[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      s_val[b] = gemm_scale_value<FMT>(sc[b], &sigma[b]);
+      if (sel_bits != nullptr) sigma[b] = (selbyte >> ((((k0 + 16 * b) >> sshift)) & 7)) & 1u;
+    }
+    const uint32_t cw[8] = {cw4[0].x, cw4[0].y, cw4[0].z, cw4[0].w, cw4[1].x, cw4[1].y, cw4[1].z, cw4[1].w};
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {  // columns k0 + 8t .. k0 + 8t + 7: four code bytes
+      const int b = t / 2;
+      const float2* tab = &sm.pair[sigma[b]][0][rep];
+      uint32_t a32[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t byte = (cw[t] >> (8 * i)) & 0xFFu;
+        const float2 p = tab[byte * kGemmReplicas];
+        a32[i] = pack_bf16(p.x * s_val[b], p.y * s_val[b]);
+      }
+      bf16x8 a;
+      __builtin_memcpy(&a, a32, 16);
+#pragma unroll
+      for (int j = 0; j < MT; ++j) {
+        const int m = 16 * j + r;
+        uint4 xv = make_uint4(0, 0, 0, 0);
+        if (in_k && m < M) xv = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k0 + 8 * t);
+        bf16x8 bv;
+        __builtin_memcpy(&bv, &xv, 16);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[j], 0, 0, 0);
+      }
+    }
+  }
+  // this lane holds D[4q + e][r] of its tile: layer rows sub*16 + 4q + e, x row 16j + r
+#pragma unroll
+  for (int j = 0; j < MT; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) atomicAdd(&sm.y[sub * 16 + 4 * q + e][16 * j + r], acc[j][e]);
+  __syncthreads();
+  const int rows = NS * 16;
+  for (int i = tid; i < rows * MT * 16; i += kGemmBlock) {
+    const int row = i % rows, m = i / rows;
+    if (n_base + row < N && m < M) y[(int64_t)m * ldy + n_base + row] = sm.y[row][m];
+  }
+}
+
+int log2i(int v) {
+  int s = 0;
+  while (v > 1) { v >>= 1; ++s; }
+  return s;
+}
+
+template <int FMT>
+hipError_t launch_mt(int mt, dim3 grid, hipStream_t stream, const uint16_t* x, int64_t ldx, int M,
+                     const uint8_t* codes, const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
+                     const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
+                     int NS) {
+  if (mt == 1)
+    gemm_w4a16_kernel<FMT, 1><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
+                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
+  else if (mt == 2)
+    gemm_w4a16_kernel<FMT, 2><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
+                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
+  else
+    gemm_w4a16_kernel<FMT, 4><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
+                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
+                             const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
+                             int64_t N, int64_t K, int group_size, int sel_size, int fmt, float* y, int64_t ldy,
+                             hipStream_t stream) {
+  if (M == 0 || N == 0) return hipSuccess;
+  if (K == 0) {
+    for (int64_t m = 0; m < M; ++m) {
+      hipError_t e = launch_fill_zero(y + m * ldy, (size_t)N * sizeof(float), stream);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  static int cus = 0;  // compute units of the device, asked once (256 on MI355X)
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    cus = hipGetDevice(&dev) == hipSuccess &&
+                  hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0
+              ? n
+              : 256;
+  }
+  // row tiles per block: as many as still leave a block for every compute unit
+  int NS = kGemmWaves;
+  while (NS > 1 && (N + 16 * NS - 1) / (16 * NS) < cus) NS /= 2;
+  const dim3 grid((unsigned)((N + 16 * NS - 1) / (16 * NS)));
+  const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
+  const uint16_t* xp = static_cast<const uint16_t*>(x);
+  for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time
+    const int rows = (int)(M - m0 < 64 ? M - m0 : 64);
+    const int mt = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
+    hipError_t e;
+    if (fmt == 0)
+      e = launch_mt<0>(mt, grid, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
+                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, NS);
+    else
+      e = launch_mt<1>(mt, grid, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
+                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, NS);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace aaac

@@ -653,6 +653,111 @@ def test_gemv_w4a16_cfg1_full_size():
     assert np.abs(host(y) - exact).mean() < 0.2 * np.abs(exact).mean()
 
 
+# ------------------------------------------ the W4A16 product on the matrix cores
+
+def synthetic_quantised_layer(N, K, g, S, fmt, seed, exact=False):
+    """Codes, scales, selection bits and tables drawn directly (no fit).  exact: integer tables and
+    power-of-two scales, so that with small integer activations every sum is exact in fp32."""
+    gen = torch.Generator(device=DEV).manual_seed(seed)
+    codes = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    sign = torch.randint(0, 2, (N, K // g), device=DEV, generator=gen)
+    if S < g:
+        bits = torch.randint(0, 256, (N, A.sel_stride(K, S)), dtype=torch.uint8, device=DEV, generator=gen)
+        sign = torch.zeros_like(sign)
+    else:
+        bits = None
+    if fmt == A.NVFP4:
+        mag = torch.full((N, K // g), 0x38, device=DEV) if exact else torch.randint(1, 0x60, (N, K // g), device=DEV, generator=gen)
+        scales = (mag | (sign << 7)).to(torch.uint8)
+    else:
+        if exact:
+            mag = torch.full((N, K // g), 0x3F80, device=DEV)
+        else:
+            mag = (torch.rand((N, K // g), device=DEV, generator=gen) * 0.02 + 1e-3).to(torch.bfloat16).view(torch.int16).int() & 0x7FFF
+        scales = (mag | (sign << 15)).to(torch.int32).to(torch.int16)
+    if exact:
+        t = torch.cat([torch.arange(-8, 8, device=DEV).float(), torch.arange(-7, 9, device=DEV).float() * 2])
+    else:
+        t = torch.sort(torch.randn((2, 16), device=DEV, generator=gen) * 3, dim=1)[0].reshape(32)
+    tb = t.to(torch.bfloat16).view(torch.int16)
+    return tb, codes, scales, bits
+
+
+def oracle_args(x, codes, scales, bits, tb, fmt):
+    return (inputs.bits(x), host(codes), host(scales).view(np.uint8 if fmt == 0 else np.uint16),
+            None if bits is None else host(bits), u16(tb))
+
+
+@pytest.mark.parametrize("N,K,g,S,fmt,M", [
+    (64, 256, 16, 16, 0, 16),
+    (100, 320, 16, 16, 0, 5),       # ragged rows and a partial chunk of 64 columns
+    (33, 64, 64, 64, 1, 1),         # one lane quarter of columns
+    (200, 1024, 128, 16, 1, 33),    # selection bits from the bit array, three tiles of x rows
+    (48, 2048, 32, 32, 0, 64),
+    (130, 4096, 128, 128, 1, 70),   # x in two batches of 64 rows
+    (20, 512, 16, 16, 1, 17),       # bf16 scales with groups of 16
+    (5000, 512, 64, 32, 1, 8),      # many rows: several row tiles per block
+])
+def test_gemm_w4a16_exact_on_integer_data_and_bounded_on_real_data(N, K, g, S, fmt, M):
+    say(f"[gemm] N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
+    # integer tables, unit scales, small integer activations: every partial sum is an integer
+    # below 2^24, so the result is exact whatever the order of the additions
+    tb, codes, scales, bits = synthetic_quantised_layer(N, K, g, S, fmt, 900 + N, exact=True)
+    x = torch.randint(-4, 5, (M, K), device=DEV).to(torch.bfloat16)
+    y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, S, fmt)
+    torch.cuda.synchronize()
+    ref, mag = oracle.gemm_w4a16(*oracle_args(x, codes, scales, bits, tb, fmt), g, S, fmt)
+    assert mag.max() < 2 ** 24 and (host(y) == ref).all()
+    # real-valued tables, scales and activations: any summation order of K exact products stays within
+    # (K - 1) roundings, plus the 8 adds of the cross-wavefront reduction
+    tb, codes, scales, bits = synthetic_quantised_layer(N, K, g, S, fmt, 950 + N)
+    x = torch.randn((M, K), device=DEV).to(torch.bfloat16)
+    y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, S, fmt)
+    torch.cuda.synchronize()
+    ref, mag = oracle.gemm_w4a16(*oracle_args(x, codes, scales, bits, tb, fmt), g, S, fmt)
+    err = np.abs(host(y).astype(np.float64) - ref)
+    assert (err <= (K + 8) * 2.0 ** -24 * mag + np.spacing(np.abs(ref))).all()
+    assert np.median(err / (mag + 1e-30)) < 16 * 2.0 ** -24      # and far inside it for the typical output
+
+
+def test_gemm_w4a16_unit_vectors_return_the_stored_dequantised_weights():
+    # x = e_k: y[m, n] is the bf16 weight aaac_dequant stores, exactly (rounding of T * s included)
+    N, K, g, fmt = 70, 576, 16, 0
+    Wt = inputs.make_weight(N, K, "student5", 41, DEV)
+    I = torch.rand(K, device=DEV) + 0.05
+    tb, codes, scales, bits = quantise_on_gpu(Wt, I, g, g, fmt)
+    ks = [0, 1, 7, 8, 63, 64, 100, 255, 256, 300, 511, 512, 575]
+    x = torch.zeros((len(ks), K), dtype=torch.bfloat16, device=DEV)
+    for m, k in enumerate(ks):
+        x[m, k] = 1.0
+    y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, g, fmt)
+    What = A.aaac_dequant(codes, scales, tb, g, fmt)
+    torch.cuda.synchronize()
+    for m, k in enumerate(ks):
+        assert (y[m] == What[:, k].float()).all(), k
+
+
+def test_gemm_w4a16_cfg1_full_size_matches_the_product_with_the_dequantised_layer():
+    cfg = inputs.CONFIGS[1]
+    l = cfg["layers"][0]
+    g, fmt = cfg["g"], cfg["fmt"]
+    Wt = inputs.layer_weights(l, DEV)
+    I = torch.rand(l["K"], device=DEV) * 100 + 1
+    tb, codes, scales, bits = quantise_on_gpu(Wt, I, g, g, fmt)
+    x = torch.randn((32, l["K"]), device=DEV).to(torch.bfloat16)
+    y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, g, fmt)
+    torch.cuda.synchronize()
+    rows = np.arange(0, l["N"], 97)
+    ref, mag = oracle.gemm_w4a16(inputs.bits(x), host(codes)[rows], host(scales).view(np.uint16)[rows], None, u16(tb),
+                                 g, g, fmt)
+    err = np.abs(host(y)[:, rows].astype(np.float64) - ref)
+    assert (err <= (l["K"] + 8) * 2.0 ** -24 * mag + np.spacing(np.abs(ref))).all()
+    # all outputs against torch's fp64 product with the stored dequantised weights
+    What = A.aaac_dequant(codes, scales, tb, g, fmt).double()
+    full = host(x.double() @ What.T)
+    assert np.abs(host(y) - full).max() <= 1e-4 * np.abs(full).max()
+
+
 # ------------------------------------------ benchmark settings, full size
 
 def test_config0_full():
