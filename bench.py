@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--gemv-rows", type=int, default=0,
                     help="after the timed steps, also time aaac_gemv_w4a16 (the quantised layers applied to this many "
                          "rows of activations) and report it as gemv_w4a16")
+    ap.add_argument("--gemm-rows", type=int, default=0,
+                    help="the same for aaac_gemm_w4a16 (matrix cores, weights rounded to bf16), reported as gemm_w4a16")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
@@ -209,18 +211,21 @@ def main():
         iter_us = assign_ms * 1e3 / n_outer
         weights_per_s_iter = n_w / (iter_us * 1e-6)
 
-    gemv = None
-    if args.gemv_rows > 0:
-        # the quantised layers of the last step applied to a few activation rows; 20 calls per layer
+    def time_product(Mx, matrix_cores):
+        # the quantised layers of the last step applied to Mx activation rows; 20 calls per layer
         # are captured in a HIP graph so that the host's call overhead does not hide the kernel
-        Mx = args.gemv_rows
-        xs = {L["name"]: torch.randn((Mx, L["K"]), device=dev).to(torch.bfloat16) for L in layers}
-        ys = {L["name"]: torch.empty((Mx, L["N"]), dtype=torch.float32, device=dev) for L in layers}
         side = torch.cuda.Stream()
         per_layer = []
         for L in layers:
-            call = lambda st: A.aaac_gemv_w4a16(xs[L["name"]], L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt,
-                                                y=ys[L["name"]], stream=st)
+            xs = torch.randn((Mx, L["K"]), device=dev).to(torch.bfloat16)
+            ys = torch.empty((Mx, L["N"]), dtype=torch.float32, device=dev)
+            if matrix_cores:
+                wsx = torch.empty(max(A.aaac_gemm_w4a16_workspace(Mx, L["K"]), 256), dtype=torch.uint8, device=dev)
+                call = lambda st: A.aaac_gemm_w4a16(xs, L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt, y=ys,
+                                                    ws=wsx, stream=st)
+            else:
+                call = lambda st: A.aaac_gemv_w4a16(xs, L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt, y=ys,
+                                                    stream=st)
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
                 call(side)
@@ -238,8 +243,12 @@ def main():
             us = e0.elapsed_time(e1) * 1e3 / 20
             nbytes = L["N"] * L["K"] * (0.5 + (1 if fmt == A.NVFP4 else 2) / g + (1 / (8 * S) if S < g else 0))
             per_layer.append({"layer": L["name"], "us": us, "weights_per_s": L["N"] * L["K"] / (us * 1e-6),
-                              "hbm_GBs": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS})
-        gemv = {"rows_of_x": Mx, "bound": "hbm", "peak_GBs": HBM_PEAK_GBS, "layers": per_layer}
+                              "hbm_GBs": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                              "TFLOPs": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12})
+        return {"rows_of_x": Mx, "bound": "hbm", "peak_GBs": HBM_PEAK_GBS, "layers": per_layer}
+
+    gemv = time_product(args.gemv_rows, False) if args.gemv_rows > 0 else None
+    gemm = time_product(args.gemm_rows, True) if args.gemm_rows > 0 else None
 
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -287,6 +296,8 @@ def main():
         out["refine_roofline"] = refine
     if gemv is not None:
         out["gemv_w4a16"] = gemv
+    if gemm is not None:
+        out["gemm_w4a16"] = gemm
     if quant is not None:
         out["quantile_init"] = quant
         out["config"]["init"] = "quantile"

@@ -216,12 +216,16 @@ int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
  *   y[m, n] = sum_k x[m, k] * w^[n, k]
  * so the result is the fp32-accumulated product of x with the dequantised layer, without
  * that layer ever being written.  x is taken 64 rows at a time (larger M re-reads the
- * codes M/64 times).  Arguments and errors as aaac_gemv_w4a16, except K % 64 == 0 and
- * scales 8-byte aligned. */
+ * codes M/64 times).  Arguments and errors as aaac_gemv_w4a16, except K % 64 == 0,
+ * scales 8-byte aligned, and
+ *   ws       dev scratch of aaac_gemm_w4a16_workspace(M, K) bytes, 256-byte aligned (x
+ *            is first copied into the matrix instruction's operand order); too small or
+ *            misaligned is AAAC_ERR_WORKSPACE. */
+size_t aaac_gemm_w4a16_workspace(int64_t M, int64_t K);
 int aaac_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
                     const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
-                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
-                    void* hip_stream);
+                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy, void* ws,
+                    size_t ws_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -68,8 +68,11 @@ def library():
         L.aaac_quantile_init.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _P, _P, _SZ, _P]
         L.aaac_gemv_w4a16.restype = _INT
         L.aaac_gemv_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64, _P]
+        L.aaac_gemm_w4a16_workspace.restype = _SZ
+        L.aaac_gemm_w4a16_workspace.argtypes = [_I64, _I64]
         L.aaac_gemm_w4a16.restype = _INT
-        L.aaac_gemm_w4a16.argtypes = L.aaac_gemv_w4a16.argtypes
+        L.aaac_gemm_w4a16.argtypes = [_P, _I64, _I64, _P, _P, _P, _I64, _P, _I64, _I64, _INT, _INT, _INT, _P, _I64, _P,
+                                      _SZ, _P]
         L.aaac_encode_sel.restype = _INT
         L.aaac_encode_sel.argtypes = [_P, _I64, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P, _I64, _P]
         L.aaac_dequant_sel.restype = _INT
@@ -283,14 +286,7 @@ def aaac_quantile_init(W, group_size, fmt, grid=None, ws=None, stream=None):
     return grid
 
 
-def aaac_gemm_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None):
-    """x bf16 [M, K] times the quantised layer on the matrix cores (weights rounded to bf16) -> y fp32 [M, N]."""
-    return aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y, stream,
-                           _entry="aaac_gemm_w4a16")
-
-
-def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None,
-                    _entry="aaac_gemv_w4a16"):
+def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, stream=None):
     """x bf16 [M, K] times the quantised layer -> y fp32 [M, N]."""
     assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
     M, K = x.shape
@@ -300,7 +296,29 @@ def aaac_gemv_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_siz
     ldx = x.stride(0) if M > 1 else max(x.stride(0), K)
     ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
     stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
-    _check(getattr(library(), _entry)(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
-                                      _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy,
-                                      _stream(stream)), _entry)
+    _check(library().aaac_gemv_w4a16(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
+                                     _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy,
+                                     _stream(stream)), "aaac_gemv_w4a16")
+    return y
+
+
+def aaac_gemm_w4a16_workspace(M, K):
+    return library().aaac_gemm_w4a16_workspace(M, K)
+
+
+def aaac_gemm_w4a16(x, codes, scales, sel_bits, tables_bf16, group_size, sel_size, fmt, y=None, ws=None, stream=None):
+    """x bf16 [M, K] times the quantised layer on the matrix cores (weights rounded to bf16) -> y fp32 [M, N]."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    M, K = x.shape
+    N = codes.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(aaac_gemm_w4a16_workspace(M, K), x.device)
+    ldx = x.stride(0) if M > 1 else max(x.stride(0), K)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    stride = 0 if sel_bits is None else (sel_bits.stride(0) if N > 1 else max(sel_bits.stride(0), sel_bits.shape[1]))
+    _check(library().aaac_gemm_w4a16(_dp(x), M, ldx, _dp(codes), _dp(scales), _dp(sel_bits), stride,
+                                     _dp(tables_bf16), N, K, group_size, sel_size, fmt, _dp(y), ldy, _dp(ws),
+                                     ws.numel(), _stream(stream)), "aaac_gemm_w4a16")
     return y

@@ -58,7 +58,7 @@ int check_layer(const aaac_layer_t& l, int group_size) {
 int w4a16_entry(bool matrix_cores, const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
                 const void* scales, const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
                 int64_t N, int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
-                void* hip_stream) {
+                void* ws, size_t ws_bytes, void* hip_stream) {
   if (tables_bf16 == nullptr) return AAAC_ERR_NULL;
   if (M > 0 && N > 0 && (y == nullptr || (K > 0 && (x == nullptr || codes == nullptr || scales == nullptr))))
     return AAAC_ERR_NULL;
@@ -74,9 +74,13 @@ int w4a16_entry(bool matrix_cores, const void* x, int64_t M, int64_t ldx, const 
   if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
   if (!aligned(x, 16) || !aligned(codes, 16) || !aligned(scales, matrix_cores ? 8 : 4) || !aligned(y, 4))
     return AAAC_ERR_SHAPE;
+  if (matrix_cores && M > 0 && N > 0 && K > 0) {
+    const int rc = check_ws(ws, ws_bytes, aaac::gemm_w4a16_workspace(M, K));
+    if (rc) return rc;
+  }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   return from_hip(matrix_cores ? aaac::launch_gemm_w4a16(x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16,
-                                                         N, K, group_size, sel_size, fmt, y, ldy, stream)
+                                                         N, K, group_size, sel_size, fmt, y, ldy, ws, stream)
                                : aaac::launch_gemv_w4a16(x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16,
                                                          N, K, group_size, sel_size, fmt, y, ldy, stream));
 }
@@ -279,15 +283,17 @@ int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
                     int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
                     void* hip_stream) {
   return w4a16_entry(false, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, group_size, sel_size,
-                     fmt, y, ldy, hip_stream);
+                     fmt, y, ldy, nullptr, 0, hip_stream);
 }
+
+size_t aaac_gemm_w4a16_workspace(int64_t M, int64_t K) { return aaac::gemm_w4a16_workspace(M, K); }
 
 int aaac_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
                     const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
-                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
-                    void* hip_stream) {
+                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy, void* ws,
+                    size_t ws_bytes, void* hip_stream) {
   return w4a16_entry(true, x, M, ldx, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, group_size, sel_size,
-                     fmt, y, ldy, hip_stream);
+                     fmt, y, ldy, ws, ws_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -11,10 +11,14 @@
 // over k may run in any order as long as A and B agree, so per 256-column chunk a lane
 // takes the 64 consecutive columns 64q..64q+63 of its row (two 16-byte code loads: the
 // four lanes of a row read one 128-byte line) and feeds them in eight steps of 8;
-// the lane that holds x row r takes the same columns of x.  A block of 8 wavefronts is
-// NS row tiles x 8/NS slices of the chunks (NS chosen by the host: many rows -> 8 tiles
-// that read the same x at the same time and share it in the L1 cache; few rows ->
-// more slices of K), reduced through a tile in LDS.
+// the lane that holds x row r takes the same columns of x (a small kernel first copies x
+// into that order, so that an operand load is one contiguous kilobyte).  A wavefront owns NT tiles of
+// 16 layer rows, so a loaded x operand feeds NT matrix instructions; the codes of the
+// next chunk are loaded while the current one is worked on.  A block of 8 wavefronts is
+// NSW wavefronts side by side along the rows x 8/NSW slices of the chunk sequence (NSW
+// chosen by the host: many rows -> wide blocks whose wavefronts read the same x at the
+// same time and share it in the L1 cache; few rows -> more slices of K), reduced
+// through a tile in LDS.
 //
 // Two codes are dequantised with one LDS read (code byte -> fp32 pair of table
 // values), multiplied by the scale (exact: 8 x 8 significant bits) and rounded to
@@ -63,13 +67,41 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return u;
 }
 
-// MT: tiles of 16 rows of x held at once (M <= 16 * MT in this launch); NS: row tiles per block.
-template <int FMT, int MT>
+// What a lane loads per 256-column chunk for one of its layer rows: 32 code bytes (its 64
+// columns), the scale codes of the four 16-column blocks, the byte with their selection bits.
+struct ChunkRegs {
+  uint4 c0, c1;
+  uint32_t sc[4];
+  uint32_t selbyte;
+};
+
+// x in the order the matrix instruction wants it: element ((c * 8 + st) * MT + j) * 64 + lane of
+// the packed array is the 16-byte B operand of lane (r, q) for chunk c, step st, x tile j, i.e.
+// x[16 j + r][256 c + 64 q + 8 st .. + 7] (zero outside the matrix), so that a wavefront's operand
+// load is one contiguous kilobyte.
+template <int MT>
+__global__ void pack_x_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K, int chunks,
+                              uint4* __restrict__ xpack) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)chunks * 8 * MT * 64) return;
+  const int lane = (int)(i & 63), r = lane & 15, q = lane >> 4;
+  const int64_t rest = i >> 6;
+  const int j = (int)(rest % MT), st = (int)((rest / MT) & 7), c = (int)(rest / (MT * 8));
+  const int m = 16 * j + r, k = c * kChunkCols + 64 * q + 8 * st;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (m < M && k < K) v = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k);
+  xpack[i] = v;
+}
+
+// MT: tiles of 16 rows of x held at once (M <= 16 * MT in this launch); NT: tiles of 16 layer
+// rows per wavefront (each loaded x operand feeds NT matrix instructions); NSW: wavefronts of
+// the block that stand side by side along the rows (the other 8 / NSW slice the chunks).
+template <int FMT, int MT, int NT>
 __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
-    const uint16_t* __restrict__ x, int64_t ldx, int M, const uint8_t* __restrict__ codes,
+    const uint4* __restrict__ xpack, int M, const uint8_t* __restrict__ codes,
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
-    int64_t ldy, int NS) {
+    int64_t ldy, int NSW) {
   __shared__ GemmLds<MT> sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
@@ -82,93 +114,133 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
   __syncthreads();
 
   const int r = lane & 15, q = lane >> 4;
-  const int KS = kGemmWaves / NS;            // slices of the chunk sequence
-  const int sub = wave % NS, slice = wave / NS;
-  const int n_base = blockIdx.x * 16 * NS;
-  const int n = n_base + sub * 16 + r;       // the layer row this lane dequantises
-  const bool has_row = n < N;
+  const int KS = kGemmWaves / NSW;           // slices of the chunk sequence
+  const int side = wave % NSW, slice = wave / NSW;
+  const int n_base = blockIdx.x * 16 * NT * NSW;
+  const int row0 = side * 16 * NT;           // first row of this wavefront inside the block's tile
   const int Gs = K >> gshift;
   const int rep = lane & (kGemmReplicas - 1);
   const int64_t row_bytes = K / 2;
   const int chunks = (K + kChunkCols - 1) / kChunkCols;
 
-  f32x4 acc[MT];
+  f32x4 acc[NT][MT];
 #pragma unroll
-  for (int j = 0; j < MT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int c = slice; c < chunks; c += KS) {
-    const int k0 = c * kChunkCols + 64 * q;  // this lane's 64 columns
-    const bool in_k = k0 < K;                // K % 64 == 0: all 64 or none
-    uint4 cw4[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-    uint32_t sc[4] = {0, 0, 0, 0};           // scale code of each 16-column block
-    uint32_t selbyte = 0;
-    if (in_k && has_row) {
-      const uint8_t* cp = codes + (int64_t)n * row_bytes + k0 / 2;
-      cw4[0] = *reinterpret_cast<const uint4*>(cp);
-      cw4[1] = *reinterpret_cast<const uint4*>(cp + 16);
-      const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
-      if (gshift == 4) {  // four scale groups in the lane's 64 columns
-        if (FMT == 0) {
-          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(scales) + g0);
-          sc[0] = v & 0xFFu; sc[1] = (v >> 8) & 0xFFu; sc[2] = (v >> 16) & 0xFFu; sc[3] = v >> 24;
-        } else {
-          const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(scales) + g0);
-          sc[0] = v.x & 0xFFFFu; sc[1] = v.x >> 16; sc[2] = v.y & 0xFFFFu; sc[3] = v.y >> 16;
+  auto fetch = [&](ChunkRegs (&cr)[NT], int c) {
+    const int k0 = c * kChunkCols + 64 * q;  // this lane's 64 columns (K % 64 == 0: all 64 or none)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int n = n_base + row0 + 16 * t + r;
+      cr[t].c0 = make_uint4(0, 0, 0, 0);
+      cr[t].c1 = make_uint4(0, 0, 0, 0);
+      cr[t].sc[0] = cr[t].sc[1] = cr[t].sc[2] = cr[t].sc[3] = 0;
+      cr[t].selbyte = 0;
+      if (c < chunks && k0 < K && n < N) {
+        const uint8_t* cp = codes + (int64_t)n * row_bytes + k0 / 2;
+        cr[t].c0 = *reinterpret_cast<const uint4*>(cp);
+        cr[t].c1 = *reinterpret_cast<const uint4*>(cp + 16);
+        const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
+        uint32_t* sc = cr[t].sc;
+        if (gshift == 4) {  // four scale groups in the lane's 64 columns
+          if (FMT == 0) {
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(scales) + g0);
+            sc[0] = v & 0xFFu; sc[1] = (v >> 8) & 0xFFu; sc[2] = (v >> 16) & 0xFFu; sc[3] = v >> 24;
+          } else {
+            const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(scales) + g0);
+            sc[0] = v.x & 0xFFFFu; sc[1] = v.x >> 16; sc[2] = v.y & 0xFFFFu; sc[3] = v.y >> 16;
+          }
+        } else if (gshift == 5) {  // two
+          if (FMT == 0) {
+            const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
+            sc[0] = sc[1] = v & 0xFFu; sc[2] = sc[3] = v >> 8;
+          } else {
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
+            sc[0] = sc[1] = v & 0xFFFFu; sc[2] = sc[3] = v >> 16;
+          }
+        } else {  // one
+          const uint32_t v = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
+                                      : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
+          sc[0] = sc[1] = sc[2] = sc[3] = v;
         }
-      } else if (gshift == 5) {  // two
-        if (FMT == 0) {
-          const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
-          sc[0] = sc[1] = v & 0xFFu; sc[2] = sc[3] = v >> 8;
-        } else {
-          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
-          sc[0] = sc[1] = v & 0xFFFFu; sc[2] = sc[3] = v >> 16;
+        if (sel_bits != nullptr) cr[t].selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
+      }
+    }
+  };
+  auto work = [&](const ChunkRegs (&cr)[NT], int c) {
+    const int k0 = c * kChunkCols + 64 * q;
+    const uint4* xc = xpack + (int64_t)c * 8 * MT * 64 + lane;
+    float s_val[NT][4];
+    uint32_t sigma[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        s_val[t][b] = gemm_scale_value<FMT>(cr[t].sc[b], &sigma[t][b]);
+        if (sel_bits != nullptr) sigma[t][b] = (cr[t].selbyte >> (((k0 + 16 * b) >> sshift) & 7)) & 1u;
+      }
+    // the x operands of several steps are loaded together, ahead of the dequantisation that needs
+    // no memory: eight steps at a time while they fit the registers, else four
+    constexpr int kPhase = MT <= 2 ? 8 : 4;
+#pragma unroll
+    for (int ph = 0; ph < 8 / kPhase; ++ph) {
+      uint4 xv[kPhase][MT];
+#pragma unroll
+      for (int u = 0; u < kPhase; ++u)
+#pragma unroll
+        for (int j = 0; j < MT; ++j) xv[u][j] = xc[((ph * kPhase + u) * MT + j) * 64];
+#pragma unroll
+      for (int u = 0; u < kPhase; ++u) {  // columns k0 + 8 st .. k0 + 8 st + 7: four code bytes per row
+        const int st = ph * kPhase + u;
+        const int b = st / 2;
+        bf16x8 bv[MT];
+#pragma unroll
+        for (int j = 0; j < MT; ++j) __builtin_memcpy(&bv[j], &xv[u][j], 16);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const uint32_t cw = st < 4 ? (st == 0 ? cr[t].c0.x : st == 1 ? cr[t].c0.y : st == 2 ? cr[t].c0.z : cr[t].c0.w)
+                                     : (st == 4 ? cr[t].c1.x : st == 5 ? cr[t].c1.y : st == 6 ? cr[t].c1.z : cr[t].c1.w);
+          const float2* tab = &sm.pair[sigma[t][b]][0][rep];
+          uint32_t a32[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t byte = (cw >> (8 * i)) & 0xFFu;
+            const float2 p = tab[byte * kGemmReplicas];
+            a32[i] = pack_bf16(p.x * s_val[t][b], p.y * s_val[t][b]);
+          }
+          bf16x8 a;
+          __builtin_memcpy(&a, a32, 16);
+#pragma unroll
+          for (int j = 0; j < MT; ++j)
+            acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv[j], acc[t][j], 0, 0, 0);
         }
-      } else {  // one
-        const uint32_t v = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
-                                    : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
-        sc[0] = sc[1] = sc[2] = sc[3] = v;
-      }
-      if (sel_bits != nullptr) selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
-    }
-    float s_val[4];
-    uint32_t sigma[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      s_val[b] = gemm_scale_value<FMT>(sc[b], &sigma[b]);
-      if (sel_bits != nullptr) sigma[b] = (selbyte >> ((((k0 + 16 * b) >> sshift)) & 7)) & 1u;
-    }
-    const uint32_t cw[8] = {cw4[0].x, cw4[0].y, cw4[0].z, cw4[0].w, cw4[1].x, cw4[1].y, cw4[1].z, cw4[1].w};
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {  // columns k0 + 8t .. k0 + 8t + 7: four code bytes
-      const int b = t / 2;
-      const float2* tab = &sm.pair[sigma[b]][0][rep];
-      uint32_t a32[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t byte = (cw[t] >> (8 * i)) & 0xFFu;
-        const float2 p = tab[byte * kGemmReplicas];
-        a32[i] = pack_bf16(p.x * s_val[b], p.y * s_val[b]);
-      }
-      bf16x8 a;
-      __builtin_memcpy(&a, a32, 16);
-#pragma unroll
-      for (int j = 0; j < MT; ++j) {
-        const int m = 16 * j + r;
-        uint4 xv = make_uint4(0, 0, 0, 0);
-        if (in_k && m < M) xv = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k0 + 8 * t);
-        bf16x8 bv;
-        __builtin_memcpy(&bv, &xv, 16);
-        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[j], 0, 0, 0);
       }
     }
+  };
+  // the codes of the next chunk are on their way while this one is worked on
+  ChunkRegs ca[NT], cb[NT];
+  int c = slice;
+  fetch(ca, c);
+  while (c < chunks) {
+    fetch(cb, c + KS);
+    work(ca, c);
+    c += KS;
+    if (c >= chunks) break;
+    fetch(ca, c + KS);
+    work(cb, c);
+    c += KS;
   }
-  // this lane holds D[4q + e][r] of its tile: layer rows sub*16 + 4q + e, x row 16j + r
+  // this lane holds D[4q + e][r] of each tile: layer rows row0 + 16 t + 4q + e, x row 16 j + r
 #pragma unroll
-  for (int j = 0; j < MT; ++j)
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) atomicAdd(&sm.y[sub * 16 + 4 * q + e][16 * j + r], acc[j][e]);
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) atomicAdd(&sm.y[row0 + 16 * t + 4 * q + e][16 * j + r], acc[t][j][e]);
   __syncthreads();
-  const int rows = NS * 16;
+  const int rows = NSW * NT * 16;
   for (int i = tid; i < rows * MT * 16; i += kGemmBlock) {
     const int row = i % rows, m = i / rows;
     if (n_base + row < N && m < M) y[(int64_t)m * ldy + n_base + row] = sm.y[row][m];
@@ -181,29 +253,54 @@ int log2i(int v) {
   return s;
 }
 
-template <int FMT>
-hipError_t launch_mt(int mt, dim3 grid, hipStream_t stream, const uint16_t* x, int64_t ldx, int M,
-                     const uint8_t* codes, const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
-                     const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
-                     int NS) {
-  if (mt == 1)
-    gemm_w4a16_kernel<FMT, 1><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
-                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
-  else if (mt == 2)
-    gemm_w4a16_kernel<FMT, 2><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
-                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
-  else
-    gemm_w4a16_kernel<FMT, 4><<<grid, kGemmBlock, 0, stream>>>(x, ldx, M, codes, scales, sel_bits, sel_stride,
-                                                              tables_bf16, N, K, gshift, sshift, y, ldy, NS);
+template <int FMT, int MT, int NT>
+hipError_t launch_tiles(hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
+                        const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
+                        const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
+                        uint4* xpack, int cus) {
+  const int chunks = (K + kChunkCols - 1) / kChunkCols;
+  const int64_t items = (int64_t)chunks * 8 * MT * 64;
+  pack_x_kernel<MT><<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(x, ldx, M, K, chunks, xpack);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // wavefronts side by side along the rows: as many as still leave a block for every compute unit,
+  // at most 8 / NT (the block's tile in LDS holds 128 rows)
+  int nsw = kGemmWaves / NT;
+  while (nsw > 1 && (N + 16 * NT * nsw - 1) / (16 * NT * nsw) < cus) nsw /= 2;
+  const unsigned grid = (unsigned)((N + 16 * NT * nsw - 1) / (16 * NT * nsw));
+  gemm_w4a16_kernel<FMT, MT, NT><<<grid, kGemmBlock, 0, stream>>>(xpack, M, codes, scales, sel_bits, sel_stride,
+                                                                 tables_bf16, N, K, gshift, sshift, y, ldy, nsw);
   return hipGetLastError();
+}
+
+template <int FMT>
+hipError_t launch_mt(int mt, hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
+                     const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
+                     const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
+                     uint4* xpack, int cus) {
+  if (mt == 1)
+    return launch_tiles<FMT, 1, 1>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
+                                   sshift, y, ldy, xpack, cus);
+  if (mt == 2)
+    return launch_tiles<FMT, 2, 2>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
+                                   sshift, y, ldy, xpack, cus);
+  return launch_tiles<FMT, 4, 2>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
+                                 sshift, y, ldy, xpack, cus);
 }
 
 }  // namespace
 
+size_t gemm_w4a16_workspace(int64_t M, int64_t K) {
+  if (M <= 0 || K <= 0) return 0;
+  const int64_t chunks = (K + kChunkCols - 1) / kChunkCols;
+  const int64_t mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+  return (size_t)(chunks * 8 * mt * 64 * 16);
+}
+
 hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
                              const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
                              int64_t N, int64_t K, int group_size, int sel_size, int fmt, float* y, int64_t ldy,
-                             hipStream_t stream) {
+                             void* ws, hipStream_t stream) {
   if (M == 0 || N == 0) return hipSuccess;
   if (K == 0) {
     for (int64_t m = 0; m < M; ++m) {
@@ -220,22 +317,19 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
               ? n
               : 256;
   }
-  // row tiles per block: as many as still leave a block for every compute unit
-  int NS = kGemmWaves;
-  while (NS > 1 && (N + 16 * NS - 1) / (16 * NS) < cus) NS /= 2;
-  const dim3 grid((unsigned)((N + 16 * NS - 1) / (16 * NS)));
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
-  for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time
+  uint4* xpack = static_cast<uint4*>(ws);
+  for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time (the packed copy is reused)
     const int rows = (int)(M - m0 < 64 ? M - m0 : 64);
     const int mt = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
     hipError_t e;
     if (fmt == 0)
-      e = launch_mt<0>(mt, grid, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
-                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, NS);
+      e = launch_mt<0>(mt, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
+                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
     else
-      e = launch_mt<1>(mt, grid, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
-                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, NS);
+      e = launch_mt<1>(mt, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
+                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -113,9 +113,11 @@ hipError_t launch_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
                              hipStream_t stream);
 
 // The same product on the matrix cores, dequantised weights rounded to bf16; K % 64 == 0.
+// ws: gemm_w4a16_workspace(M, K) bytes for the copy of x in operand order.
+size_t gemm_w4a16_workspace(int64_t M, int64_t K);
 hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
                              const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16,
                              int64_t N, int64_t K, int group_size, int sel_size, int fmt, float* y, int64_t ldy,
-                             hipStream_t stream);
+                             void* ws, hipStream_t stream);
 
 }  // namespace aaac

@@ -129,9 +129,13 @@ def test_other_entry_points_validate():
     assert gemv(g=64, S=16, bits=FAKE, stride=0) == E_SHAPE
     assert gemv(fmt=9) == E_ARG
     assert gemv(codes=ctypes.c_void_p(0x10008)) == E_SHAPE   # codes not 16-byte aligned
-    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 96, 16, 16, 0, FAKE, 8, None) == E_SHAPE  # K % 64
-    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, ctypes.c_void_p(0x10004), None, 0, FAKE, 8, 128, 16, 16, 0, FAKE, 8, None) == E_SHAPE
-    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 128, 64, 16, 0, FAKE, 8, None) == E_NULL
+    W = ctypes.c_void_p(0x20000)
+    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 96, 16, 16, 0, FAKE, 8, W, 1 << 20, None) == E_SHAPE  # K % 64
+    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, ctypes.c_void_p(0x10004), None, 0, FAKE, 8, 128, 16, 16, 0, FAKE, 8, W, 1 << 20, None) == E_SHAPE
+    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 128, 64, 16, 0, FAKE, 8, W, 1 << 20, None) == E_NULL
+    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 128, 16, 16, 0, FAKE, 8, W, 64, None) == E_WS
+    assert L.aaac_gemm_w4a16(FAKE, 2, 128, FAKE, FAKE, None, 0, FAKE, 8, 128, 16, 16, 0, FAKE, 8, None, 0, None) == E_WS
+    assert L.aaac_gemm_w4a16_workspace(2, 128) == 8 * 64 * 16 and L.aaac_gemm_w4a16_workspace(64, 8192) == 32 * 8 * 4 * 64 * 16
     # selection groups: a size that divides the scale group, 16..128
     assert L.aaac_fit_nested(arr, 1, 16, 32, 0, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE  # larger than the scale group
     assert L.aaac_fit_nested(arr, 1, 64, 8, 1, gp, 1, 1, FAKE, 1 << 20, None) == E_SHAPE
