@@ -303,6 +303,54 @@ def test_whole_path_can_be_captured_in_a_graph_and_replayed():
                                ref.view(torch.uint8) if ref.dtype == torch.bfloat16 else ref), rep
 
 
+def test_alg1_in_full_and_both_products_can_be_captured_in_a_graph():
+    """Quantile initialisation, both loops, small selection groups, encode with selection bits and
+    the two W4A16 products: kernels only, so a graph replay must reproduce the eager results."""
+    N, K, g, S, fmt = 300, 1024, 128, 16, 1
+    Wt = inputs.make_weight(N, K, "gauss_outlier", 23, DEV)
+    I = torch.rand(K, device=DEV) + 0.05
+    x1 = torch.randn((1, K), device=DEV).to(torch.bfloat16)
+    x9 = torch.randn((9, K), device=DEV).to(torch.bfloat16)
+    layers, ((tf, tb, ob),) = A.make_layers([Wt], [I], 2)
+    ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt, sel_size=S), dtype=torch.uint8, device=DEV)
+    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=DEV)
+    scales = torch.empty((N, K // g), dtype=torch.int16, device=DEV)
+    bits = torch.empty((N, A.sel_stride(K, S)), dtype=torch.uint8, device=DEV)
+    y1 = torch.empty((1, N), device=DEV)
+    y9 = torch.empty((9, N), device=DEV)
+    wsx = torch.empty(A.aaac_gemm_w4a16_workspace(9, K), dtype=torch.uint8, device=DEV)
+
+    def run():
+        A.aaac_fit_nested(layers, g, fmt, None, 2, 3, ws, sel_size=S)
+        A.aaac_encode_sel(Wt, g, S, fmt, I, tb, codes, scales, bits)
+        A.aaac_gemv_w4a16(x1, codes, scales, bits, tb, g, S, fmt, y=y1)
+        A.aaac_gemm_w4a16(x9, codes, scales, bits, tb, g, S, fmt, y=y9, ws=wsx)
+
+    run()
+    torch.cuda.synchronize()
+    outs = (tb, codes, scales, bits, y9)
+    want = [t.clone() for t in outs]
+    want_y1 = y1.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        for t in outs + (y1, tf):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs[:4], want[:4]):
+            assert torch.equal(got, ref), rep
+        # the products add in an order that may differ between runs (LDS atomics): compare closely
+        assert torch.allclose(y9, want[4], rtol=1e-4, atol=1e-5) and torch.allclose(y1, want_y1, rtol=1e-4, atol=1e-5)
+
+
 def test_batch_matches_single_calls():
     cfg = inputs.scaled_config(inputs.CONFIGS[3], rows_div=64, tokens_div=512)
     Ws = [inputs.layer_weights(l, DEV) for l in cfg["layers"]]
