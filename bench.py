@@ -10,11 +10,19 @@ tokens, INT4 group 128, 20 iterations); --config selects another of the five
 benchmark settings.
 
 Prints one JSON line.  `value` is weight-iterations per second over the whole
-step (sum of N*K over the layers * iterations / step time).  `roofline`
-describes the Lloyd-iteration kernel: its average duration is measured with HIP
-events on the launch stream around every fit call inside the timed region (fit
-time / iterations, so launch gaps and the small scale / init / final-table
-kernels count against it).  `cpu_baseline` is the CPU oracle, single-threaded.
+step (sum of N*K over the layers * passes over the weights / step time).
+`roofline` describes the Lloyd-iteration kernel: its average duration is measured
+with HIP events on the launch stream around every fit call inside the timed
+region (fit time / iterations, so launch gaps and the small scale / init /
+final-table kernels count against it).  `cpu_baseline` is the CPU oracle,
+single-threaded.
+
+Options beyond the default path (each adds its own object to the line):
+--n-inner / --n-outer run both loops of the learning algorithm (refine_roofline:
+the refinement pass), --sel-size one table choice per that many weights with
+separate selection bits, --quantile-init the quantile tables as the start
+(quantile_init), --gemv-rows / --gemm-rows the quantised layers applied to
+activation rows (gemv_w4a16, gemm_w4a16).
 """
 import argparse
 import json
@@ -306,7 +314,7 @@ def main():
         import oracle
         # bounded sample: the oracle's fit of (a row slice of) the first layer, all iterations
         L = layers[0]
-        rows = min(L["N"], max(1, int(4.0e8 / (L["K"] * passes))))  # about 20 s at ~50 ns per weight-iteration
+        rows = min(L["N"], max(1, int(8.0e8 / (L["K"] * passes))))  # 10-20 s at 15-25 ns per weight-iteration
         Wb = inputs.bits(L["W"][:rows])
         Ih = Is[L["x"]].cpu().numpy()
         t1 = time.perf_counter()
