@@ -19,7 +19,11 @@
 //
 // Parity pins: every function here is pinned by tests/test_oracle_*.py
 // (closed forms, brute force, exact rational centroids, hand-derived vectors,
-// library bf16/fp8 conversions, textbook 1-D Lloyd).  The method as a whole has
+// library bf16/fp8 conversions, textbook 1-D Lloyd; for the quantile
+// initialisation a library quantile routine and exact rational interpolation;
+// for the selection bit array a hand-worked vector and brute-force errors of the
+// small groups; for the W4A16 products a matmul of weights rebuilt with library
+// conversions, unit vectors and a hand-worked product).  The method as a whole has
 // no printed intermediate values in the paper to compare with: whole-method
 // results against the paper's tables are "parity unpinned".
 
