@@ -113,7 +113,9 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
 }
 
 struct SelectLds {
-  unsigned long long cum[kQuantSlots * 256];  // pass 1: 4096 prefix sums; later: the staged histograms
+  // pass 1: 4096 prefix sums; later: the staged histograms, bin b of slot s at s * 272 + b + b / 16
+  // (runs of 16 bins start in different banks)
+  unsigned long long cum[kQuantSlots * 272];
   unsigned long long lane_total[64];
   unsigned long long part[kQuantSlots][16];
   unsigned long long rank[kQuantSlots];
@@ -132,40 +134,56 @@ __global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __res
   const int tid = threadIdx.x, lane = tid & 63;
   const int U = tg.count;
   if (PASS == 1) {
-    // exclusive prefix sums of the 4096 counters: 64 lanes x 64 consecutive bins
-    for (int i = tid; i < 4096; i += kQBlock) sm.cum[i] = qs->hist1[i];
+    // exclusive prefix sums of the 4096 counters: 64 lanes x 64 consecutive bins; counter i sits at
+    // i + i / 64, so that the lanes' runs start in different banks
+    auto pad = [](int i) { return i + (i >> 6); };
+    {  // four counters per thread, loaded together
+      unsigned long long v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = qs->hist1[tid + k * kQBlock];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) sm.cum[pad(tid + k * kQBlock)] = v[k];
+    }
     __syncthreads();
-    if (tid < 64) {
+    if (tid < 64) {  // 16 counters at a time go to registers first, so that the LDS reads overlap
       unsigned long long s = 0;
-      for (int j = 0; j < 64; ++j) {
-        const unsigned long long n = sm.cum[lane * 64 + j];
-        sm.cum[lane * 64 + j] = s;
-        s += n;
+#pragma unroll
+      for (int j0 = 0; j0 < 64; j0 += 16) {
+        unsigned long long n[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) n[j] = sm.cum[lane * 65 + j0 + j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          sm.cum[lane * 65 + j0 + j] = s;
+          s += n[j];
+        }
       }
       sm.lane_total[lane] = s;
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned long long s = 0;
-      for (int j = 0; j < 64; ++j) {
-        const unsigned long long n = sm.lane_total[j];
-        sm.lane_total[j] = s;
-        s += n;
+    if (tid < 64) {  // exclusive scan of the 64 lane totals across the first wavefront
+      const unsigned long long mine = sm.lane_total[lane];
+      unsigned long long incl = mine;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
       }
+      sm.lane_total[lane] = incl - mine;
     }
     __syncthreads();
-    for (int i = tid; i < 4096; i += kQBlock) sm.cum[i] += sm.lane_total[i / 64];
+    for (int i = tid; i < 4096; i += kQBlock) sm.cum[pad(i)] += sm.lane_total[i / 64];
     __syncthreads();
     if (tid < U) {  // the last bin whose prefix sum does not exceed the rank
       const unsigned long long rank = tg.rank[tid];
       int lo = 0, hi = 4095;
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (sm.cum[mid] <= rank) lo = mid; else hi = mid - 1;
+        if (sm.cum[pad(mid)] <= rank) lo = mid; else hi = mid - 1;
       }
       sm.bin[tid] = (uint32_t)lo;
       sm.prefix[tid] = (uint32_t)lo;
-      sm.rank[tid] = rank - sm.cum[lo];
+      sm.rank[tid] = rank - sm.cum[pad(lo)];
     }
     for (int i = tid; i < 4096; i += kQBlock) qs->hist1[i] = 0;
     for (int i = tid; i < 4096 / 4; i += kQBlock) reinterpret_cast<uint32_t*>(qs->map1)[i] = 0xFFFFFFFFu;
@@ -173,10 +191,22 @@ __global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __res
     constexpr int kBins = PassBits<PASS>::bins;
     // slots are handed out in ascending order, so the last target holds the highest one in use
     const int used = (int)qs->slot[U - 1] + 1;
-    for (int i = tid; i < used * kBins; i += kQBlock) {
-      const int at = (i / kBins) * 256 + (i % kBins);
-      sm.cum[at] = (&qs->hist[0][0])[at];
-      (&qs->hist[0][0])[at] = 0;
+    {  // the counters of the slots in use, every thread's loads issued together
+      constexpr int kPerThread = kQuantSlots * kBins / kQBlock;  // 16 (256 bins) or 1 (16 bins)
+      unsigned long long v[kPerThread];
+      int at[kPerThread];
+#pragma unroll
+      for (int k = 0; k < kPerThread; ++k) {
+        const int i = tid + k * kQBlock;
+        at[k] = (i / kBins) * 256 + (i % kBins);
+        v[k] = i < used * kBins ? (&qs->hist[0][0])[at[k]] : 0ull;
+      }
+#pragma unroll
+      for (int k = 0; k < kPerThread; ++k) {
+        const int b = at[k] & 255;
+        sm.cum[(at[k] >> 8) * 272 + b + (b >> 4)] = v[k];
+        if (tid + k * kQBlock < used * kBins) (&qs->hist[0][0])[at[k]] = 0;
+      }
     }
     if (tid < U) {
       sm.rank[tid] = qs->rank[tid];
@@ -191,10 +221,10 @@ __global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __res
       constexpr int kSeg = kBins / 16;
       const int u = tid >> 4, j = tid & 15;
       const bool live = u < U;
-      const unsigned long long* h = sm.cum + (live ? (int)sm.slot[u] : 0) * 256;
+      const unsigned long long* h = sm.cum + (live ? (int)sm.slot[u] : 0) * 272;  // bin b at h[b + b / 16]
       unsigned long long part = 0;
 #pragma unroll
-      for (int b = 0; b < kSeg; ++b) part += h[j * kSeg + b];
+      for (int b = 0; b < kSeg; ++b) part += h[j * kSeg + b + ((j * kSeg + b) >> 4)];
       sm.part[u][j] = part;
       __syncthreads();
       if (live && j == 0) {
@@ -209,7 +239,7 @@ __global__ __launch_bounds__(kQBlock) void quant_select_kernel(QuantState* __res
         int bin = seg * kSeg;
         for (int b = 0; b < kSeg; ++b) {  // and the last such bin inside it
           if (below <= rank) { bin = seg * kSeg + b; taken = below; }
-          below += h[seg * kSeg + b];
+          below += h[seg * kSeg + b + ((seg * kSeg + b) >> 4)];
         }
         sm.bin[u] = (uint32_t)bin;
         sm.prefix[u] = (sm.prefix[u] << (kBins == 16 ? 4 : 8)) | (uint32_t)bin;
@@ -310,7 +340,7 @@ hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw
   if (e != hipSuccess) return e;
   const int64_t chunks = N * (K / 8);
   int64_t blocks = ceil_div(chunks, 4 * kQBlock);  // at least four chunks per thread
-  if (blocks > 512) blocks = 512;
+  if (blocks > 256) blocks = 256;  // one block per compute unit: every block merges its counters with global atomics
   const int64_t per_block = ceil_div(ceil_div(chunks, blocks), kQBlock) * kQBlock;
   blocks = ceil_div(chunks, per_block);
 #define AAAC_QPASS(P)                                                                                          \
