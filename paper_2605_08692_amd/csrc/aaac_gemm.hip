@@ -247,6 +247,146 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Large batches of activation rows (prefill-sized M): a tiled matrix product.  A block of 4
+// wavefronts owns 128 layer rows x 128 x rows and walks K in stages of 64 columns.  Per stage
+// every thread dequantises 32 weights of one layer row into a bf16 tile in LDS and copies 32
+// activations of one x row into a second tile, so the dequantisation is paid once per 128 rows
+// of x; then each wavefront multiplies its 64 x 64 quarter (4 x 4 tiles of 16 x 16, two
+// k-steps of 32) with operands read from LDS.  A tile row is 64 bf16 = eight 16-byte units;
+// unit u of row r is stored at unit u ^ (r & 7), so that the 8 lanes served per clock, which
+// read the same unit of 8 consecutive rows, fall into different banks.
+constexpr int kTileN = 128, kTileM = 128, kTileK = 64;
+constexpr int kTiledFrom = 64;  // batches above this many rows of x take the tiled kernel
+constexpr int kTiledBlock = 256;
+
+struct alignas(16) TiledLds {
+  float2 pair[2][256][kGemmReplicas];
+  uint4 a[kTileN][8];   // dequantised weights, bf16, swizzled units
+  uint4 b[kTileM][8];   // activations, bf16, swizzled units
+  float T[32];
+};
+
+template <int FMT>
+__global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int M, const uint8_t* __restrict__ codes,
+    const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
+    const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
+    int64_t ldy) {
+  __shared__ TiledLds sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
+  __syncthreads();
+  for (int i = tid; i < 2 * 256 * kGemmReplicas; i += kTiledBlock) {
+    const int b = (i / kGemmReplicas) & 255, t = i / (256 * kGemmReplicas);
+    (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
+  }
+  __syncthreads();
+
+  const int n_base = blockIdx.x * kTileN, m_base = blockIdx.y * kTileM;
+  // loader role: row of both tiles and which half (32 columns) of the stage
+  const int lrow = tid >> 1, half = tid & 1;
+  const int n = n_base + lrow, m = m_base + lrow;
+  const bool has_n = n < N, has_m = m < M;
+  const int Gs = K >> gshift;
+  const int rep = lane & (kGemmReplicas - 1);
+  const uint8_t* crow = codes + (int64_t)(has_n ? n : 0) * (K / 2);
+  const uint16_t* xrow = x + (int64_t)(has_m ? m : 0) * ldx;
+  // multiplier role: quarter of the block tile
+  const int r = lane & 15, q = lane >> 4;
+  const int wn = (wave >> 1) * 64, wm = (wave & 1) * 64;
+
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int k_stage = 0; k_stage < K; k_stage += kTileK) {
+    const int k0 = k_stage + 32 * half;
+    // dequantise 32 weights of row n: two 16-column blocks with their scale and selection
+    uint4 cw4 = make_uint4(0, 0, 0, 0);
+    uint32_t sc0 = 0, sc1 = 0, selbyte = 0;
+    if (has_n) {
+      cw4 = *reinterpret_cast<const uint4*>(crow + k0 / 2);
+      const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
+      if (gshift == 4) {
+        if (FMT == 0) {
+          const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
+          sc0 = v & 0xFFu; sc1 = v >> 8;
+        } else {
+          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
+          sc0 = v & 0xFFFFu; sc1 = v >> 16;
+        }
+      } else {
+        sc0 = sc1 = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
+                             : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
+      }
+      if (sel_bits != nullptr) selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
+    }
+    uint4 xv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      xv[u] = make_uint4(0, 0, 0, 0);
+      if (has_m) xv[u] = *reinterpret_cast<const uint4*>(xrow + k0 + 8 * u);
+    }
+    const uint32_t cw[4] = {cw4.x, cw4.y, cw4.z, cw4.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // unit u: columns k0 + 8u .. k0 + 8u + 7
+      const int blk = u / 2;
+      uint32_t sigma;
+      const float s_val = gemm_scale_value<FMT>(blk == 0 ? sc0 : sc1, &sigma);
+      if (sel_bits != nullptr) sigma = (selbyte >> (((k0 + 16 * blk) >> sshift) & 7)) & 1u;
+      const float2* tab = &sm.pair[sigma][0][rep];
+      uint32_t a32[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t byte = (cw[u] >> (8 * i)) & 0xFFu;
+        const float2 p = tab[byte * kGemmReplicas];
+        a32[i] = pack_bf16(p.x * s_val, p.y * s_val);
+      }
+      const int unit = (4 * half + u) ^ (lrow & 7);
+      sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
+      sm.b[lrow][unit] = xv[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 af[4], bfv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = wn + 16 * i + r;
+        const uint4 v = sm.a[row][(4 * ks + q) ^ (row & 7)];
+        __builtin_memcpy(&af[i], &v, 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = wm + 16 * j + r;
+        const uint4 v = sm.b[row][(4 * ks + q) ^ (row & 7)];
+        __builtin_memcpy(&bfv[j], &v, 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e, x row m_base + wm + 16 j + r
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int mm = m_base + wm + 16 * j + r;
+    if (mm >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int nn = n_base + wn + 16 * i + 4 * q + e;
+        if (nn < N) y[(int64_t)mm * ldy + nn] = acc[i][j][e];
+      }
+  }
+}
+
 int log2i(int v) {
   int s = 0;
   while (v > 1) { v >>= 1; ++s; }
@@ -319,6 +459,18 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   }
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
+  if (M > kTiledFrom) {  // large batches: tiles of 128 x 128, dequantised once per 128 rows of x
+    const dim3 grid((unsigned)((N + kTileN - 1) / kTileN), (unsigned)((M + kTileM - 1) / kTileM));
+    if (fmt == 0)
+      gemm_w4a16_tiled_kernel<0><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride,
+                                                                   tables_bf16, (int)N, (int)K, log2i(group_size),
+                                                                   log2i(sel_size), y, ldy);
+    else
+      gemm_w4a16_tiled_kernel<1><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride,
+                                                                   tables_bf16, (int)N, (int)K, log2i(group_size),
+                                                                   log2i(sel_size), y, ldy);
+    return hipGetLastError();
+  }
   uint4* xpack = static_cast<uint4*>(ws);
   for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time (the packed copy is reused)
     const int rows = (int)(M - m0 < 64 ? M - m0 : 64);

@@ -745,6 +745,10 @@ def oracle_args(x, codes, scales, bits, tb, fmt):
     (130, 4096, 128, 128, 1, 70),   # x in two batches of 64 rows
     (20, 512, 16, 16, 1, 17),       # bf16 scales with groups of 16
     (5000, 512, 64, 32, 1, 8),      # many rows: several row tiles per block
+    (300, 320, 16, 16, 0, 130),     # more than 64 rows of x: the tiled kernel, ragged tiles in both directions
+    (128, 1024, 128, 16, 1, 256),   # tiled, selection bits from the bit array
+    (77, 640, 32, 32, 1, 65),       # tiled, one partial tile each way
+    (260, 2048, 16, 16, 1, 200),    # tiled, bf16 scales with groups of 16
 ])
 def test_gemm_w4a16_exact_on_integer_data_and_bounded_on_real_data(N, K, g, S, fmt, M):
     say(f"[gemm] N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
