@@ -44,6 +44,7 @@ LANE_OPS_PER_WEIGHT = 33.0
 LANE_OPS_PER_WEIGHT_REFINE = 15.0
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 lanes x 2.4 GHz, one op per lane-clock
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 
 
 def bytes_per_weight(g):
@@ -252,8 +253,12 @@ def main():
             nbytes = L["N"] * L["K"] * (0.5 + (1 if fmt == A.NVFP4 else 2) / g + (1 / (8 * S) if S < g else 0))
             per_layer.append({"layer": L["name"], "us": us, "weights_per_s": L["N"] * L["K"] / (us * 1e-6),
                               "hbm_GBs": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                              "TFLOPs": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12})
-        return {"rows_of_x": Mx, "bound": "hbm", "peak_GBs": HBM_PEAK_GBS, "layers": per_layer}
+                              "TFLOPs": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12,
+                              "mfma_frac": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS})
+        # a few rows of x: bound by reading the codes once (HBM); many rows: by the matrix cores
+        bound = "mfma" if matrix_cores and Mx > 64 else "hbm"
+        return {"rows_of_x": Mx, "bound": bound, "peak_GBs": HBM_PEAK_GBS, "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                "layers": per_layer}
 
     gemv = time_product(args.gemv_rows, False) if args.gemv_rows > 0 else None
     gemm = time_product(args.gemm_rows, True) if args.gemm_rows > 0 else None

@@ -23,6 +23,8 @@
 // Two codes are dequantised with one LDS read (code byte -> fp32 pair of table
 // values), multiplied by the scale (exact: 8 x 8 significant bits) and rounded to
 // bf16 pairs by the hardware conversion.
+#include <cmath>
+
 #include "aaac_device.h"
 #include "aaac_internal.h"
 
@@ -256,24 +258,26 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
 // k-steps of 32) with operands read from LDS.  A tile row is 64 bf16 = eight 16-byte units;
 // unit u of row r is stored at unit u ^ (r & 7), so that the 8 lanes served per clock, which
 // read the same unit of 8 consecutive rows, fall into different banks.
-constexpr int kTileN = 128, kTileM = 128, kTileK = 64;
-constexpr int kTiledFrom = 64;  // batches above this many rows of x take the tiled kernel
+constexpr int kTileN = 128, kTileK = 64;  // the tile's x rows (128 or 256) are a template parameter
 constexpr int kTiledBlock = 256;
 
+template <int BM>
 struct alignas(16) TiledLds {
   float2 pair[2][256][kGemmReplicas];
   uint4 a[kTileN][8];   // dequantised weights, bf16, swizzled units
-  uint4 b[kTileM][8];   // activations, bf16, swizzled units
+  uint4 b[BM][8];       // activations, bf16, swizzled units
   float T[32];
 };
 
-template <int FMT>
+template <int FMT, int BM>
 __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int M, const uint8_t* __restrict__ codes,
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
     int64_t ldy) {
-  __shared__ TiledLds sm;
+  __shared__ TiledLds<BM> sm;
+  constexpr int kXRows = BM / 128;  // x rows a thread copies per stage
+  constexpr int kMJ = BM / 32;      // 16-row x tiles per wavefront
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   __syncthreads();
@@ -283,31 +287,36 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
   }
   __syncthreads();
 
-  const int n_base = blockIdx.x * kTileN, m_base = blockIdx.y * kTileM;
+  const int n_base = blockIdx.x * kTileN, m_base = blockIdx.y * BM;
   // loader role: row of both tiles and which half (32 columns) of the stage
   const int lrow = tid >> 1, half = tid & 1;
-  const int n = n_base + lrow, m = m_base + lrow;
-  const bool has_n = n < N, has_m = m < M;
+  const int n = n_base + lrow;
+  const bool has_n = n < N;
   const int Gs = K >> gshift;
   const int rep = lane & (kGemmReplicas - 1);
   const uint8_t* crow = codes + (int64_t)(has_n ? n : 0) * (K / 2);
-  const uint16_t* xrow = x + (int64_t)(has_m ? m : 0) * ldx;
   // multiplier role: quarter of the block tile
   const int r = lane & 15, q = lane >> 4;
-  const int wn = (wave >> 1) * 64, wm = (wave & 1) * 64;
+  const int wn = (wave >> 1) * 64, wm = (wave & 1) * (BM / 2);
 
-  f32x4 acc[4][4];
+  f32x4 acc[4][kMJ];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < kMJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int k_stage = 0; k_stage < K; k_stage += kTileK) {
+  // what a thread loads per stage: 16 code bytes, their scale codes and selection byte, 32 activations
+  // of one or two x rows
+  struct StageRegs {
+    uint4 cw4;
+    uint32_t sc0, sc1, selbyte;
+    uint4 xv[kXRows][4];
+  };
+  auto fetch = [&](StageRegs& sr, int k_stage) {
     const int k0 = k_stage + 32 * half;
-    // dequantise 32 weights of row n: two 16-column blocks with their scale and selection
     uint4 cw4 = make_uint4(0, 0, 0, 0);
     uint32_t sc0 = 0, sc1 = 0, selbyte = 0;
-    if (has_n) {
+    if (has_n && k_stage < K) {
       cw4 = *reinterpret_cast<const uint4*>(crow + k0 / 2);
       const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
       if (gshift == 4) {
@@ -324,19 +333,32 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
       }
       if (sel_bits != nullptr) selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
     }
-    uint4 xv[4];
+    sr.cw4 = cw4;
+    sr.sc0 = sc0;
+    sr.sc1 = sc1;
+    sr.selbyte = selbyte;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      xv[u] = make_uint4(0, 0, 0, 0);
-      if (has_m) xv[u] = *reinterpret_cast<const uint4*>(xrow + k0 + 8 * u);
+    for (int xr = 0; xr < kXRows; ++xr) {
+      const int m = m_base + lrow + 128 * xr;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        sr.xv[xr][u] = make_uint4(0, 0, 0, 0);
+        if (m < M && k_stage < K) sr.xv[xr][u] = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k0 + 8 * u);
+      }
     }
-    const uint32_t cw[4] = {cw4.x, cw4.y, cw4.z, cw4.w};
+  };
+  StageRegs sr;
+  fetch(sr, 0);
+  for (int k_stage = 0; k_stage < K; k_stage += kTileK) {
+    const int k0 = k_stage + 32 * half;
+    // dequantise the 32 weights: two 16-column blocks with their scale and selection
+    const uint32_t cw[4] = {sr.cw4.x, sr.cw4.y, sr.cw4.z, sr.cw4.w};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // unit u: columns k0 + 8u .. k0 + 8u + 7
       const int blk = u / 2;
       uint32_t sigma;
-      const float s_val = gemm_scale_value<FMT>(blk == 0 ? sc0 : sc1, &sigma);
-      if (sel_bits != nullptr) sigma = (selbyte >> (((k0 + 16 * blk) >> sshift) & 7)) & 1u;
+      const float s_val = gemm_scale_value<FMT>(blk == 0 ? sr.sc0 : sr.sc1, &sigma);
+      if (sel_bits != nullptr) sigma = (sr.selbyte >> (((k0 + 16 * blk) >> sshift) & 7)) & 1u;
       const float2* tab = &sm.pair[sigma][0][rep];
       uint32_t a32[4];
 #pragma unroll
@@ -347,12 +369,14 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
       }
       const int unit = (4 * half + u) ^ (lrow & 7);
       sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
-      sm.b[lrow][unit] = xv[u];
+#pragma unroll
+      for (int xr = 0; xr < kXRows; ++xr) sm.b[lrow + 128 * xr][unit] = sr.xv[xr][u];  // 128 keeps row & 7
     }
     __syncthreads();
+    fetch(sr, k_stage + kTileK);  // the next stage's loads are in flight during the matrix instructions
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 af[4], bfv[4];
+      bf16x8 af[4], bfv[kMJ];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = wn + 16 * i + r;
@@ -360,7 +384,7 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
         __builtin_memcpy(&af[i], &v, 16);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < kMJ; ++j) {
         const int row = wm + 16 * j + r;
         const uint4 v = sm.b[row][(4 * ks + q) ^ (row & 7)];
         __builtin_memcpy(&bfv[j], &v, 16);
@@ -368,13 +392,14 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < kMJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
   // lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e, x row m_base + wm + 16 j + r
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kMJ; ++j) {
     const int mm = m_base + wm + 16 * j + r;
     if (mm >= M) continue;
 #pragma unroll
@@ -459,16 +484,30 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   }
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
-  if (M > kTiledFrom) {  // large batches: tiles of 128 x 128, dequantised once per 128 rows of x
-    const dim3 grid((unsigned)((N + kTileN - 1) / kTileN), (unsigned)((M + kTileM - 1) / kTileM));
-    if (fmt == 0)
-      gemm_w4a16_tiled_kernel<0><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride,
-                                                                   tables_bf16, (int)N, (int)K, log2i(group_size),
-                                                                   log2i(sel_size), y, ldy);
-    else
-      gemm_w4a16_tiled_kernel<1><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride,
-                                                                   tables_bf16, (int)N, (int)K, log2i(group_size),
-                                                                   log2i(sel_size), y, ldy);
+  // Large batches take the tiled kernel, which pays the dequantisation once per 128 or 256 rows of x
+  // but walks all of K inside one block; small ones take the streaming kernel, 64 rows of x per
+  // pass over the codes.  The choice compares two cost models fitted to measurements on MI355X:
+  // tiled: 1.45 us per 64-column stage for one round of blocks, or the work at 540 TFLOP/s;
+  // streaming: per pass 30 us + 0.4 ps per weight.
+  const double work = (double)N * (double)K;
+  const double tiled_us = fmax((double)(K / kTileK) * 1.45, 2.0 * (double)M * work / 540e6);
+  const double stream_us = (double)((M + 63) / 64) * (30.0 + 0.4e-6 * work);
+  if (M > 64 && tiled_us < stream_us) {
+    // 256 rows of x per tile when that still gives every compute unit a block, else 128
+    const int64_t n_tiles = (N + kTileN - 1) / kTileN;
+    const bool wide = n_tiles * ((M + 255) / 256) >= cus;
+    const int bm = wide ? 256 : 128;
+    const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm));
+#define AAAC_TILED(FMT, BM)                                                                                      \
+  gemm_w4a16_tiled_kernel<FMT, BM><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride, \
+                                                                     tables_bf16, (int)N, (int)K, log2i(group_size),  \
+                                                                     log2i(sel_size), y, ldy)
+    if (fmt == 0) {
+      if (wide) AAAC_TILED(0, 256); else AAAC_TILED(0, 128);
+    } else {
+      if (wide) AAAC_TILED(1, 256); else AAAC_TILED(1, 128);
+    }
+#undef AAAC_TILED
     return hipGetLastError();
   }
   uint4* xpack = static_cast<uint4*>(ws);
