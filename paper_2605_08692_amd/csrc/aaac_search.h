@@ -211,19 +211,17 @@ __device__ __forceinline__ void wave_make_rows(SearchTables& st) {
 // of the block call it after wave_make_rows() and a barrier.  Ends with a barrier.
 __device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLut& sl) {
   const int tid = threadIdx.x;
-  if (tid < kBuckets) {
+  if (tid < 2 * kBuckets) {  // one thread per bucket and table
+    const int r = tid / kBuckets, b = tid % kBuckets;
+    int below = 0, inside = 0;
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      int below = 0, inside = 0;
-#pragma unroll
-      for (int j = 0; j < 15; ++j) {
-        const int bj = st.mid_bucket[r][j];
-        below += bj < tid ? 1 : 0;
-        inside += bj == tid ? 1 : 0;
-      }
-      const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
-      st.entry[r][tid] = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
+    for (int j = 0; j < 15; ++j) {
+      const int bj = st.mid_bucket[r][j];
+      below += bj < b ? 1 : 0;
+      inside += bj == b ? 1 : 0;
     }
+    const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
+    st.entry[r][b] = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
   }
   __syncthreads();
   // replicate: thread -> (replica = tid % 32, buckets tid/32 + 32*k)
