@@ -260,10 +260,14 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
 // read the same unit of 8 consecutive rows, fall into different banks.
 constexpr int kTileN = 128, kTileK = 64;  // the tile's x rows (128 or 256) are a template parameter
 constexpr int kTiledBlock = 256;
+// Copies of the pair table.  Four keep the block's LDS at 64 KB (256 rows of x) or 48 KB (128 rows), so that
+// two or three blocks share a compute unit and one block's dequantisation overlaps another's matrix
+// instructions; with eight, one 256-row block filled the compute unit alone and ran a third slower.
+constexpr int kTiledReplicas = 4;
 
 template <int BM>
 struct alignas(16) TiledLds {
-  float2 pair[2][256][kGemmReplicas];
+  float2 pair[2][256][kTiledReplicas];
   uint4 a[kTileN][8];   // dequantised weights, bf16, swizzled units
   uint4 b[BM][8];       // activations, bf16, swizzled units
   float T[32];
@@ -281,8 +285,8 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   __syncthreads();
-  for (int i = tid; i < 2 * 256 * kGemmReplicas; i += kTiledBlock) {
-    const int b = (i / kGemmReplicas) & 255, t = i / (256 * kGemmReplicas);
+  for (int i = tid; i < 2 * 256 * kTiledReplicas; i += kTiledBlock) {
+    const int b = (i / kTiledReplicas) & 255, t = i / (256 * kTiledReplicas);
     (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
   }
   __syncthreads();
@@ -293,7 +297,7 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
   const int n = n_base + lrow;
   const bool has_n = n < N;
   const int Gs = K >> gshift;
-  const int rep = lane & (kGemmReplicas - 1);
+  const int rep = lane & (kTiledReplicas - 1);
   const uint8_t* crow = codes + (int64_t)(has_n ? n : 0) * (K / 2);
   // multiplier role: quarter of the block tile
   const int r = lane & 15, q = lane >> 4;
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint32_t byte = (cw[u] >> (8 * i)) & 0xFFu;
-        const float2 p = tab[byte * kGemmReplicas];
+        const float2 p = tab[byte * kTiledReplicas];
         a32[i] = pack_bf16(p.x * s_val, p.y * s_val);
       }
       const int unit = (4 * half + u) ^ (lrow & 7);
@@ -486,16 +490,25 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   const uint16_t* xp = static_cast<const uint16_t*>(x);
   // Large batches take the tiled kernel, which pays the dequantisation once per 128 or 256 rows of x
   // but walks all of K inside one block; small ones take the streaming kernel, 64 rows of x per
-  // pass over the codes.  The choice compares two cost models fitted to measurements on MI355X:
-  // tiled: 1.45 us per 64-column stage for one round of blocks, or the work at 540 TFLOP/s;
-  // streaming: per pass 30 us + 0.4 ps per weight.
+  // pass over the codes.  The choice compares cost models fitted to measurements on MI355X.
+  // Tiled: a stage of 64 columns takes a block 1.33 us when it has the compute unit to itself and
+  // 1.95 / 2.6 us when two / three blocks share it (128 rows of x; three fit), 2.0 / 3.0 us for one /
+  // two blocks of 256 rows; the blocks run in rounds of (compute units x blocks that fit).
+  // Streaming: per pass 30 us + 0.4 ps per weight.
   const double work = (double)N * (double)K;
-  const double tiled_us = fmax((double)(K / kTileK) * 1.45, 2.0 * (double)M * work / 540e6);
+  const int64_t n_tiles = (N + kTileN - 1) / kTileN;
+  const auto tiled_us = [&](int bm, const double* per_stage, int fit) {
+    const int64_t blocks = n_tiles * ((M + bm - 1) / bm), per_round = (int64_t)cus * fit;
+    const int64_t full = blocks / per_round, rem = blocks % per_round;
+    double t = (double)full * per_stage[fit - 1];
+    if (rem > 0) t += per_stage[(rem + cus - 1) / cus - 1];
+    return t * (double)(K / kTileK);
+  };
+  static const double kNarrowStage[3] = {1.33, 1.95, 2.6}, kWideStage[2] = {2.0, 3.0};
+  const double narrow_us = tiled_us(128, kNarrowStage, 3), wide_us = tiled_us(256, kWideStage, 2);
   const double stream_us = (double)((M + 63) / 64) * (30.0 + 0.4e-6 * work);
-  if (M > 64 && tiled_us < stream_us) {
-    // 256 rows of x per tile when that still gives every compute unit a block, else 128
-    const int64_t n_tiles = (N + kTileN - 1) / kTileN;
-    const bool wide = n_tiles * ((M + 255) / 256) >= cus;
+  if (M > 64 && (narrow_us < stream_us || wide_us < stream_us)) {
+    const bool wide = wide_us < narrow_us;
     const int bm = wide ? 256 : 128;
     const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm));
 #define AAAC_TILED(FMT, BM)                                                                                      \
