@@ -680,6 +680,43 @@ def test_gemv_w4a16_unit_vectors_and_strides():
     assert (ybig[:, N:] == -7.0).all()
 
 
+def test_w4a16_every_e4m3_scale_code():
+    # hand-made codes and scales: every storable E4M3 scale (0x00..0x7E, both values of the selection
+    # bit on top) appears in every row, so the hardware FP8 conversion the products use is compared
+    # with the oracle's E4M3 decoding code by code (subnormals included)
+    N, K, g, fmt = 24, 4096, 16, 0
+    rng = np.random.default_rng(77)
+    sc = np.arange(256, dtype=np.uint8)
+    sc[sc == 0x7F] = 0x7E
+    sc[sc == 0xFF] = 0xFE
+    scales_h = np.stack([np.roll(sc, 11 * n) for n in range(N)])
+    codes_h = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    tabs = np.sort(rng.normal(0, 3, (2, 16)).astype(np.float32), axis=1).reshape(32)
+    tb = torch.from_numpy(tabs).to(DEV).to(torch.bfloat16)
+    codes, scales = torch.from_numpy(codes_h).to(DEV), torch.from_numpy(scales_h).to(DEV)
+    x = (torch.randn((3, K), device=DEV) * 2).to(torch.bfloat16)
+    y = A.aaac_gemv_w4a16(x, codes, scales, None, tb.view(torch.int16), g, g, fmt)
+    torch.cuda.synchronize()
+    ref, mag = oracle.gemv_w4a16(inputs.bits(x), codes_h, scales_h, None, u16(tb.view(torch.int16)), g, g, fmt)
+    err = np.abs(host(y).astype(np.float64) - ref)
+    assert (err <= gemv_tolerance(K, mag) + np.spacing(np.abs(ref))).all(), float((err / (mag + 1e-30)).max())
+    # unit vectors pick single dequantised weights: exact, scale by scale
+    cols = [0, 16 * 1 + 3, 16 * 7 + 9, 16 * 8, 16 * 126 + 15, 16 * 129, 16 * 254 + 1, K - 1]
+    xe = torch.zeros((len(cols), K), dtype=torch.bfloat16, device=DEV)
+    for m, k in enumerate(cols):
+        xe[m, k] = 1.0
+    ye = A.aaac_gemv_w4a16(xe, codes, scales, None, tb.view(torch.int16), g, g, fmt)
+    torch.cuda.synchronize()
+    refe, _ = oracle.gemv_w4a16(inputs.bits(xe), codes_h, scales_h, None, u16(tb.view(torch.int16)), g, g, fmt)
+    assert (host(ye).astype(np.float64) == refe).all()
+    # the matrix-core product sees the same scales
+    ws = torch.empty(max(A.aaac_gemm_w4a16_workspace(3, K), 256), dtype=torch.uint8, device=DEV)
+    yg = A.aaac_gemm_w4a16(x, codes, scales, None, tb.view(torch.int16), g, g, fmt, ws=ws)
+    torch.cuda.synchronize()
+    refg, magg = oracle.gemm_w4a16(inputs.bits(x), codes_h, scales_h, None, u16(tb.view(torch.int16)), g, g, fmt)
+    assert (np.abs(host(yg).astype(np.float64) - refg) <= (K + 8) * 2.0 ** -24 * magg + np.spacing(np.abs(refg))).all()
+
+
 def test_gemv_w4a16_cfg1_full_size():
     cfg = inputs.CONFIGS[1]
     l = cfg["layers"][0]
