@@ -73,7 +73,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // columns), the scale codes of the four 16-column blocks, the byte with their selection bits.
 struct ChunkRegs {
   uint4 c0, c1;
-  uint32_t sc[4];
+  uint2 sc;  // the raw scale bytes, taken apart where they are used
   uint32_t selbyte;
 };
 
@@ -96,9 +96,11 @@ __global__ void pack_x_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M
 }
 
 // MT: tiles of 16 rows of x held at once (M <= 16 * MT in this launch); NT: tiles of 16 layer
-// rows per wavefront (each loaded x operand feeds NT matrix instructions); NSW: wavefronts of
-// the block that stand side by side along the rows (the other 8 / NSW slice the chunks).
-template <int FMT, int MT, int NT>
+// rows per wavefront (each loaded x operand feeds NT matrix instructions); GS: log2 of the scale
+// group size, 6 standing for 64 and more (one scale per lane and chunk); SEL: selection bits come
+// from the bit array; NSW: wavefronts of the block that stand side by side along the rows (the
+// other 8 / NSW slice the chunks).
+template <int FMT, int MT, int NT, int GS, bool SEL>
 __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
     const uint4* __restrict__ xpack, int M, const uint8_t* __restrict__ codes,
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
@@ -131,47 +133,42 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
 #pragma unroll
     for (int j = 0; j < MT; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // Loads are unconditional, from clamped addresses, and their values are not touched here: a load
+  // under a branch makes the number of loads in flight unknown to the compiler, which then waits for
+  // all of them wherever it waits for one.  A row beyond N reads row N - 1 (its outputs are not
+  // stored), a chunk beyond the last reads chunk 0 (not used), columns beyond K read the row's first
+  // bytes (their x operand is zero).
   auto fetch = [&](ChunkRegs (&cr)[NT], int c) {
     const int k0 = c * kChunkCols + 64 * q;  // this lane's 64 columns (K % 64 == 0: all 64 or none)
+    const int kc = c < chunks && k0 < K ? k0 : 0;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int n = n_base + row0 + 16 * t + r;
-      cr[t].c0 = make_uint4(0, 0, 0, 0);
-      cr[t].c1 = make_uint4(0, 0, 0, 0);
-      cr[t].sc[0] = cr[t].sc[1] = cr[t].sc[2] = cr[t].sc[3] = 0;
-      cr[t].selbyte = 0;
-      if (c < chunks && k0 < K && n < N) {
-        const uint8_t* cp = codes + (int64_t)n * row_bytes + k0 / 2;
-        cr[t].c0 = *reinterpret_cast<const uint4*>(cp);
-        cr[t].c1 = *reinterpret_cast<const uint4*>(cp + 16);
-        const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
-        uint32_t* sc = cr[t].sc;
-        if (gshift == 4) {  // four scale groups in the lane's 64 columns
-          if (FMT == 0) {
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(scales) + g0);
-            sc[0] = v & 0xFFu; sc[1] = (v >> 8) & 0xFFu; sc[2] = (v >> 16) & 0xFFu; sc[3] = v >> 24;
-          } else {
-            const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(scales) + g0);
-            sc[0] = v.x & 0xFFFFu; sc[1] = v.x >> 16; sc[2] = v.y & 0xFFFFu; sc[3] = v.y >> 16;
-          }
-        } else if (gshift == 5) {  // two
-          if (FMT == 0) {
-            const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
-            sc[0] = sc[1] = v & 0xFFu; sc[2] = sc[3] = v >> 8;
-          } else {
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
-            sc[0] = sc[1] = v & 0xFFFFu; sc[2] = sc[3] = v >> 16;
-          }
-        } else {  // one
-          const uint32_t v = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
-                                      : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
-          sc[0] = sc[1] = sc[2] = sc[3] = v;
-        }
-        if (sel_bits != nullptr) cr[t].selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
+      const int n0 = n_base + row0 + 16 * t + r;
+      const int n = n0 < N ? n0 : N - 1;
+      const uint8_t* cp = codes + (int64_t)n * row_bytes + kc / 2;
+      cr[t].c0 = *reinterpret_cast<const uint4*>(cp);
+      cr[t].c1 = *reinterpret_cast<const uint4*>(cp + 16);
+      const int64_t g0 = (int64_t)n * Gs + (kc >> gshift);
+      cr[t].sc = make_uint2(0, 0);
+      if (FMT == 0) {  // 4, 2 or 1 scale bytes for the lane's 64 columns
+        const uint8_t* sp = static_cast<const uint8_t*>(scales) + g0;
+        if (GS == 4) cr[t].sc.x = *reinterpret_cast<const uint32_t*>(sp);
+        else if (GS == 5) cr[t].sc.x = *reinterpret_cast<const uint16_t*>(sp);
+        else cr[t].sc.x = *sp;
+      } else {
+        const uint16_t* sp = static_cast<const uint16_t*>(scales) + g0;
+        if (GS == 4) cr[t].sc = *reinterpret_cast<const uint2*>(sp);
+        else if (GS == 5) cr[t].sc.x = *reinterpret_cast<const uint32_t*>(sp);
+        else cr[t].sc.x = *sp;
       }
+      cr[t].selbyte = 0;
+      if (SEL) cr[t].selbyte = sel_bits[(int64_t)n * sel_stride + ((kc >> sshift) >> 3)];
     }
   };
-  auto work = [&](const ChunkRegs (&cr)[NT], int c) {
+  // The chunk after this one is asked for (into `next`) right after this chunk's last x operands:
+  // loads complete in order, so a wait for the x operands also waits for whatever was asked for
+  // before them, and leaves in flight what was asked for after them.
+  auto work = [&](const ChunkRegs (&cr)[NT], ChunkRegs (&next)[NT], int c, int c_next) {
     const int k0 = c * kChunkCols + 64 * q;
     const uint4* xc = xpack + (int64_t)c * 8 * MT * 64 + lane;
     float s_val[NT][4];
@@ -179,9 +176,13 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        s_val[t][b] = gemm_scale_value<FMT>(cr[t].sc[b], &sigma[t][b]);
-        if (sel_bits != nullptr) sigma[t][b] = (cr[t].selbyte >> (((k0 + 16 * b) >> sshift) & 7)) & 1u;
+      for (int b = 0; b < 4; ++b) {  // block b: columns k0 + 16 b .. + 15, scale number e of the lane's
+        constexpr int kW = FMT == 0 ? 8 : 16;
+        const int e = (16 * b) >> GS;
+        const uint32_t word = FMT == 1 && e >= 2 ? cr[t].sc.y : cr[t].sc.x;
+        const uint32_t code = (word >> (kW * (FMT == 1 ? e & 1 : e))) & (FMT == 0 ? 0xFFu : 0xFFFFu);
+        s_val[t][b] = gemm_scale_value<FMT>(code, &sigma[t][b]);
+        if (SEL) sigma[t][b] = (cr[t].selbyte >> (((k0 + 16 * b) >> sshift) & 7)) & 1u;
       }
     // the x operands of several steps are loaded together, ahead of the dequantisation that needs
     // no memory: eight steps at a time while they fit the registers, else four
@@ -193,6 +194,13 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
       for (int u = 0; u < kPhase; ++u)
 #pragma unroll
         for (int j = 0; j < MT; ++j) xv[u][j] = xc[((ph * kPhase + u) * MT + j) * 64];
+      if (ph == 8 / kPhase - 1) {
+        // (the two empty statements keep the compiler from moving these loads: ahead of the x operands,
+        // or down to their first use in the next chunk)
+        asm volatile("" ::: "memory");
+        fetch(next, c_next);
+        asm volatile("" ::: "memory");
+      }
 #pragma unroll
       for (int u = 0; u < kPhase; ++u) {  // columns k0 + 8 st .. k0 + 8 st + 7: four code bytes per row
         const int st = ph * kPhase + u;
@@ -222,17 +230,12 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
     }
   };
   // the codes of the next chunk are on their way while this one is worked on
-  ChunkRegs ca[NT], cb[NT];
-  int c = slice;
-  fetch(ca, c);
-  while (c < chunks) {
-    fetch(cb, c + KS);
-    work(ca, c);
-    c += KS;
-    if (c >= chunks) break;
-    fetch(ca, c + KS);
-    work(cb, c);
-    c += KS;
+  ChunkRegs cur[NT], nxt[NT];
+  fetch(cur, slice);
+  for (int c = slice; c < chunks; c += KS) {
+    work(cur, nxt, c, c + KS);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) cur[t] = nxt[t];
   }
   // this lane holds D[4q + e][r] of each tile: layer rows row0 + 16 t + 4q + e, x row 16 j + r
 #pragma unroll
@@ -422,7 +425,7 @@ int log2i(int v) {
   return s;
 }
 
-template <int FMT, int MT, int NT>
+template <int FMT, int MT, int NT, int GS, bool SEL>
 hipError_t launch_tiles(hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
                         const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
                         const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
@@ -437,24 +440,46 @@ hipError_t launch_tiles(hipStream_t stream, const uint16_t* x, int64_t ldx, int 
   int nsw = kGemmWaves / NT;
   while (nsw > 1 && (N + 16 * NT * nsw - 1) / (16 * NT * nsw) < cus) nsw /= 2;
   const unsigned grid = (unsigned)((N + 16 * NT * nsw - 1) / (16 * NT * nsw));
-  gemm_w4a16_kernel<FMT, MT, NT><<<grid, kGemmBlock, 0, stream>>>(xpack, M, codes, scales, sel_bits, sel_stride,
+  gemm_w4a16_kernel<FMT, MT, NT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpack, M, codes, scales, sel_bits, sel_stride,
                                                                  tables_bf16, N, K, gshift, sshift, y, ldy, nsw);
   return hipGetLastError();
 }
 
-template <int FMT>
+template <int FMT, int GS, bool SEL>
 hipError_t launch_mt(int mt, hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
                      const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
                      const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
                      uint4* xpack, int cus) {
   if (mt == 1)
-    return launch_tiles<FMT, 1, 1>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
-                                   sshift, y, ldy, xpack, cus);
+    return launch_tiles<FMT, 1, 1, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
+                                            gshift, sshift, y, ldy, xpack, cus);
   if (mt == 2)
-    return launch_tiles<FMT, 2, 2>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
-                                   sshift, y, ldy, xpack, cus);
-  return launch_tiles<FMT, 4, 2>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift,
-                                 sshift, y, ldy, xpack, cus);
+    return launch_tiles<FMT, 2, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
+                                            gshift, sshift, y, ldy, xpack, cus);
+  return launch_tiles<FMT, 4, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
+                                          gshift, sshift, y, ldy, xpack, cus);
+}
+
+// the streaming kernel's template parameters from the run-time format, group size and selection mode
+hipError_t launch_streaming(int fmt, int gshift, bool sel, int mt, hipStream_t stream, const uint16_t* x, int64_t ldx,
+                            int M, const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
+                            int64_t sel_stride, const uint16_t* tables_bf16, int N, int K, int sshift, float* y,
+                            int64_t ldy, uint4* xpack, int cus) {
+#define AAAC_STREAM(FMT, GS, SEL)                                                                                  \
+  return launch_mt<FMT, GS, SEL>(mt, stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift, \
+                                 sshift, y, ldy, xpack, cus)
+#define AAAC_STREAM_GS(FMT, SEL)                  \
+  if (gshift == 4) AAAC_STREAM(FMT, 4, SEL);      \
+  if (gshift == 5) AAAC_STREAM(FMT, 5, SEL);      \
+  AAAC_STREAM(FMT, 6, SEL)
+  if (fmt == 0) {
+    if (sel) { AAAC_STREAM_GS(0, true); }
+    AAAC_STREAM_GS(0, false);
+  }
+  if (sel) { AAAC_STREAM_GS(1, true); }
+  AAAC_STREAM_GS(1, false);
+#undef AAAC_STREAM_GS
+#undef AAAC_STREAM
 }
 
 }  // namespace
@@ -527,13 +552,9 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time (the packed copy is reused)
     const int rows = (int)(M - m0 < 64 ? M - m0 : 64);
     const int mt = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
-    hipError_t e;
-    if (fmt == 0)
-      e = launch_mt<0>(mt, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
-                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
-    else
-      e = launch_mt<1>(mt, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits, sel_stride, tables_bf16, (int)N,
-                       (int)K, log2i(group_size), log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
+    const hipError_t e = launch_streaming(fmt, log2i(group_size), bits != nullptr, mt, stream, xp + m0 * ldx, ldx, rows,
+                                          codes, scales, bits, sel_stride, tables_bf16, (int)N, (int)K,
+                                          log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
