@@ -11,13 +11,11 @@ benchmark settings.
 
 Prints one JSON line.  `value` is weight-iterations per second over the whole
 step (sum of N*K over the layers * passes over the weights / step time).
-`roofline` describes the Lloyd-iteration kernel: HIP events on the launch stream
-bracket every fit call inside the timed region; the same fit with one iteration,
-timed the same way right after, gives what a fit costs beyond its iterations
-(scale, init and final-table kernels), and the difference over the remaining
-iterations is the kernel's launch-to-launch time (`lloyd_iteration_us`; the plain
-quotient fit time / iterations is kept as `lloyd_iteration_us_inclusive`).
-`cpu_baseline` is the CPU oracle, single-threaded.
+`roofline` describes the Lloyd-iteration kernel: its average duration is measured
+with HIP events on the launch stream around every fit call inside the timed
+region (fit time / iterations, so launch gaps and the small scale / init /
+final-table kernels count against it).  `cpu_baseline` is the CPU oracle,
+single-threaded.
 
 Options beyond the default path (each adds its own object to the line):
 --n-inner / --n-outer run both loops of the learning algorithm (refine_roofline:
@@ -178,33 +176,7 @@ def main():
     def stage(i):
         return float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs]))
     stats_ms, fit_ms, enc_ms, deq_ms = stage(0), stage(1), stage(2), stage(3)
-    iter_us_inclusive = fit_ms * 1e3 / passes   # scale, init and final-table kernels and all launch gaps included
-    iter_us = iter_us_inclusive
-    fit_fixed_us = None
-    if not nested and passes > 1:
-        # The iteration kernel's own launch-to-launch time: the same fit with ONE iteration costs the
-        # fixed kernels (scales, init, final tables) plus one iteration, so the difference to the timed
-        # fits, over the other iterations, is one launch of the kernel and the gap to the next.
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
-        def fit_once():
-            if batch:
-                A.aaac_fit_batch(arr, g, fmt, grid, 1, ws_batch, stream)
-            else:
-                for L in layers:
-                    A.aaac_fit(L["W"], g, fmt, Is[L["x"]], grid, 1, L["tf"], L["tb"], L["obj"], L["ws"], stream)
-        fit_once()
-        e0.record(stream)
-        for _ in range(steps):
-            fit_once()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        fit1_ms = e0.elapsed_time(e1) / steps
-        iter_us = (fit_ms - fit1_ms) * 1e3 / (passes - 1)
-        fit_fixed_us = fit1_ms * 1e3 - iter_us
-        # the step's own results again, for the encode that follows in --gemv-rows / --gemm-rows
-        step()
-        torch.cuda.synchronize()
+    iter_us = fit_ms * 1e3 / passes
     weights_per_s_iter = n_w / (iter_us * 1e-6)
     value = n_w * passes / (ms_per_step * 1e-3)
 
@@ -325,8 +297,6 @@ def main():
         "stage_ms": {"act_stats": stats_ms, "fit": fit_ms, "encode": enc_ms, "dequant": deq_ms},
         "act_stats_GBs": x_bytes / (stats_ms * 1e-3) / 1e9,
         "lloyd_iteration_us": iter_us,
-        "lloyd_iteration_us_inclusive": iter_us_inclusive,
-        "fit_fixed_us": fit_fixed_us,
         "lloyd_weights_per_s": weights_per_s_iter,
         "roofline": {"bound": "alu", "kernel": "lloyd_iter_kernel", "achieved": achieved,
                      "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s", "frac": achieved / ALU_PEAK_TLANEOPS,
