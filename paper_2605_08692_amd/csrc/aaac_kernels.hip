@@ -325,7 +325,10 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
   StatsPlan p;
   p.strips = (int)ceil_div(K, kStatsCols);  // column groups of 4096
   const int64_t tok = tokens > 0 ? tokens : 1;
-  int64_t chunks = ceil_div(256, p.strips);       // about one block of 8 wavefronts per compute unit
+  // One block of 8 wavefronts per compute unit and never more blocks than the 256 compute units: a
+  // compute unit holds one block, so a 257th block would run alone after all the others (7 column
+  // groups x 37 token chunks = 259 blocks ran at 4.8 TB/s, 7 x 36 run at 6.5).
+  int64_t chunks = 256 / p.strips;
   const int64_t most = ceil_div(tok, 4 * kStatsWaves);  // at least 4 rows per wavefront
   if (chunks > most) chunks = most;
   if (chunks < 1) chunks = 1;
