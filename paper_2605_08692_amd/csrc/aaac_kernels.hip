@@ -213,6 +213,10 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
   build_bucket_table(sm.st, sm.sl);
   const float inv = sm.st.lutpar[0], off = sm.st.lutpar[1];
   const uint32_t rep4 = (uint32_t)(lane & (kReplicas - 1)) * 4u;
+  // (everything loaded so far is waited for here, so that no wait is left at the top of the loop,
+  // where it would also wait for the stores of the round before; see the end of the loop)
+  asm volatile("" ::"v"(v_next.x), "v"(v_next.y), "v"(v_next.z), "v"(v_next.w), "v"(Iv[0]), "v"(Iv[1]), "v"(Iv[2]),
+               "v"(Iv[3]), "v"(Iv[4]), "v"(Iv[5]), "v"(Iv[6]), "v"(Iv[7]));
   while (row < block_r1) {
     const uint4 v = v_next;
     const int cur = row;
@@ -240,6 +244,10 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
       const uint32_t idx = ((k / (kSlots * 8u)) & 15u) + (up ? 1u : 0u);
       packed |= idx << (4 * p);
     }
+    // The next row's weights are waited for here, before this row's stores go out: loads and stores
+    // complete in order, so a wait placed after the stores (at the top of the next round) would also
+    // wait for the stores just issued; here only the load, asked for a whole round ago, is outstanding.
+    asm volatile("" ::"v"(v_next.x), "v"(v_next.y), "v"(v_next.z), "v"(v_next.w));
     if (active) {
       *reinterpret_cast<uint32_t*>(codes + ((int64_t)cur * K + col) / 2) = packed;
       if ((lane % (SAME ? LANES : scale_lanes)) == 0) {

@@ -160,8 +160,7 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   for (int i = tid; i < 2 * 32 * kSlots; i += kLloydBlock) (&sm.hist[0][0][0])[i] = 0.0;
 
   // this block's rectangle and this wavefront's strip; the first rows are handed out
-  // statically (wavefront w takes row w / strips_per_block) and are in flight during the
-  // rest of the prologue
+  // statically (wavefront w takes row w / strips_per_block)
   const int queue = wave % strips_per_block;
   const int strip = (bid % strip_groups) * strips_per_block + queue;
   const int block_r0 = (bid / strip_groups) * rows_per_block;
@@ -177,6 +176,14 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   int row = has_strip ? block_r0 + wave / strips_per_block : block_r1;
   if (tid < strips_per_block) sm.st.next_row[tid] = block_r0 + waves_per_queue;
   uint8_t* sbase = sigma_arr ? sigma_arr + (active ? col / (8 * LANES) : 0) : nullptr;
+  if (!first && wave < kAccCopies) {
+    sm.copies[wave][lane] = acc_val;
+    if (lane == 0) sm.copies[wave][64] = acc_obj;
+  }
+  __syncthreads();
+  // The first row's weights and the importances are asked for only now: a wait for the sums above
+  // would also wait for every load asked for before it, and these come from HBM; they are in flight
+  // while the tables and the bucket table are built.
   uint4 v_next = make_uint4(0, 0, 0, 0);
   float r_next = 0.0f;
   uint32_t s_next = 0;  // the stored choice of the next row's group (refinement passes)
@@ -195,11 +202,6 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
     Iv[0] = lo.x; Iv[1] = lo.y; Iv[2] = lo.z; Iv[3] = lo.w;
     Iv[4] = hi.x; Iv[5] = hi.y; Iv[6] = hi.z; Iv[7] = hi.w;
   }
-  if (!first && wave < kAccCopies) {
-    sm.copies[wave][lane] = acc_val;
-    if (lane == 0) sm.copies[wave][64] = acc_obj;
-  }
-  __syncthreads();
   // wavefront 0 turns the sums into this iteration's tables
   if (wave == 0) {
     wave_make_tables(sm, !first, old_entry);
