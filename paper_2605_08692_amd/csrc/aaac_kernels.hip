@@ -135,21 +135,50 @@ __global__ __launch_bounds__(kBlock) void act_stats_reduce_kernel(const double* 
 
 // ---------------------------------------------------- scales (reciprocals)
 
+// Chunks of 8 weights are numbered row by row; thread t takes chunks t, t + T, t + 2T, ... (T = threads of
+// the grid, a multiple of 64, so the LANES lanes of a group stay together), four at a time with their loads
+// in flight together.  Row and column advance by additions (one division per thread, none per chunk).
+constexpr int kStreamUnroll = 4;
+struct ChunkWalk {
+  int64_t row, cc;   // row and chunk within the row
+  int64_t dr, dc;    // T / cpr, T % cpr
+  int64_t cpr;
+  __device__ __forceinline__ void step() {
+    row += dr;
+    cc += dc;
+    if (cc >= cpr) { cc -= cpr; ++row; }
+  }
+};
+__device__ __forceinline__ ChunkWalk chunk_walk(int64_t cpr) {
+  const int64_t T = (int64_t)gridDim.x * kBlock, c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  return ChunkWalk{c / cpr, c % cpr, T / cpr, T % cpr, cpr};
+}
+
 template <int LANES, int FMT>
 __global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __restrict__ W, int64_t N,
                                                             int64_t K, int64_t ldw,
                                                             float* __restrict__ rinv) {
-  const int64_t cpr = K / 8;  // chunks per row
-  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = c < N * cpr;
-  const int64_t row = active ? c / cpr : 0;
-  const int64_t col = active ? (c % cpr) * 8 : 0;
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
-  float a = group_max<LANES>(absmax8(unpack8(v)));
-  float s;
-  scale_code<FMT>(a, &s);
-  if (active && (threadIdx.x % LANES) == 0) rinv[row * (K / (8 * LANES)) + col / (8 * LANES)] = div_rn(1.0f, s);
+  ChunkWalk w = chunk_walk(K / 8);
+  const int64_t Gr = K / (8 * LANES);  // groups per row
+  while (w.row < N) {  // (rows only grow: once a thread's first chunk is past the end, all are)
+    uint4 v[kStreamUnroll];
+    int64_t row[kStreamUnroll], cc[kStreamUnroll];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) {
+      row[u] = w.row;
+      cc[u] = w.cc;
+      const int64_t r = w.row < N ? w.row : N - 1;  // past the end: re-read the last row, store nothing
+      v[u] = *reinterpret_cast<const uint4*>(W + r * ldw + w.cc * 8);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) {
+      const float a = group_max<LANES>(absmax8(unpack8(v[u])));
+      float s;
+      scale_code<FMT>(a, &s);
+      if (row[u] < N && (threadIdx.x % LANES) == 0) rinv[row[u] * Gr + cc[u] / LANES] = div_rn(1.0f, s);
+    }
+  }
 }
 
 // ----------------------------------------------------------------- encode
@@ -274,39 +303,51 @@ __global__ __launch_bounds__(kSearchBlock) void encode_kernel(
 template <int FMT, bool BITS>
 __global__ __launch_bounds__(kBlock) void dequant_kernel(
     const uint8_t* __restrict__ codes, const void* __restrict__ scales,
-    const uint8_t* __restrict__ sel_bits, int64_t sel_stride, int sel_size,
-    const uint16_t* __restrict__ tables_bf16, int64_t N, int64_t K, int group_size,
+    const uint8_t* __restrict__ sel_bits, int64_t sel_stride, int sshift,
+    const uint16_t* __restrict__ tables_bf16, int64_t N, int64_t K, int gshift,
     uint16_t* __restrict__ W_hat, int64_t ldo) {
   __shared__ float sT[32];
   if (threadIdx.x < 32) sT[threadIdx.x] = __uint_as_float((uint32_t)tables_bf16[threadIdx.x] << 16);
   __syncthreads();
-  const int64_t cpr = K / 8;
-  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (c >= N * cpr) return;
-  const int64_t row = c / cpr, col = (c % cpr) * 8;
-  const int64_t g = row * (K / group_size) + col / group_size;
-  uint32_t sc, sigma;
-  float s;
-  if (FMT == 0) {
-    sc = static_cast<const uint8_t*>(scales)[g];
-    sigma = sc >> 7;
-    s = e4m3_value(sc & 0x7Fu);
-  } else {
-    sc = static_cast<const uint16_t*>(scales)[g];
-    sigma = sc >> 15;
-    s = __uint_as_float((sc & 0x7FFFu) << 16);
-  }
-  if (BITS) {
-    const int64_t j = col / sel_size;
-    sigma = (sel_bits[row * sel_stride + (j >> 3)] >> (j & 7)) & 1u;
-  }
-  const uint32_t packed = *reinterpret_cast<const uint32_t*>(codes + (row * K + col) / 2);
-  const float* T = sT + 16 * sigma;
-  uint32_t h[8];
+  ChunkWalk w = chunk_walk(K / 8);
+  const int64_t Gs = K >> gshift;
+  while (w.row < N) {
+    // the loads of four chunks go out together (unconditional: past the end the last row is read again)
+    uint32_t packed[kStreamUnroll], sc[kStreamUnroll], sb[kStreamUnroll];
+    int64_t row[kStreamUnroll], col[kStreamUnroll];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) h[p] = bf16_rne(T[(packed >> (4 * p)) & 15u] * s);
-  uint4 out = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-  *reinterpret_cast<uint4*>(W_hat + row * ldo + col) = out;
+    for (int u = 0; u < kStreamUnroll; ++u) {
+      row[u] = w.row;
+      col[u] = w.cc * 8;
+      const int64_t r = w.row < N ? w.row : N - 1;
+      const int64_t g = r * Gs + (col[u] >> gshift);
+      sc[u] = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g] : (uint32_t) static_cast<const uint16_t*>(scales)[g];
+      sb[u] = 0;
+      if (BITS) sb[u] = sel_bits[r * sel_stride + ((col[u] >> sshift) >> 3)];
+      packed[u] = *reinterpret_cast<const uint32_t*>(codes + (r * K + col[u]) / 2);
+      w.step();
+    }
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) {
+      uint32_t sigma;
+      float s;
+      if (FMT == 0) {
+        sigma = sc[u] >> 7;
+        s = e4m3_value(sc[u] & 0x7Fu);
+      } else {
+        sigma = sc[u] >> 15;
+        s = __uint_as_float((sc[u] & 0x7FFFu) << 16);
+      }
+      if (BITS) sigma = (sb[u] >> ((col[u] >> sshift) & 7)) & 1u;
+      const float* T = sT + 16 * sigma;
+      uint32_t h[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) h[p] = bf16_rne(T[(packed[u] >> (4 * p)) & 15u] * s);
+      if (row[u] < N)
+        *reinterpret_cast<uint4*>(W_hat + row[u] * ldo + col[u]) =
+            make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+  }
 }
 
 // Plain fill, used instead of a memset node so that callers may capture the
@@ -349,6 +390,13 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K) {
 
 // -------------------------------------------------------------- launchers
 
+// Blocks for the kernels that walk chunks of 8 weights with a grid-sized stride: enough for every thread
+// to take about kStreamUnroll chunks, at most 8 blocks per compute unit (256 of them).
+unsigned stream_blocks(int64_t chunks) {
+  const int64_t want = ceil_div(chunks, (int64_t)kBlock * kStreamUnroll);
+  return (unsigned)(want < 1 ? 1 : want > 2048 ? 2048 : want);
+}
+
 #define AAAC_LAUNCH_CHECK()                     \
   do {                                          \
     hipError_t e_ = hipGetLastError();          \
@@ -374,7 +422,7 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
 template <int LANES>
 static hipError_t launch_rinv_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt, float* rinv,
                                     hipStream_t stream) {
-  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  const unsigned gblocks = stream_blocks(N * (K / 8));
   if (fmt == 0)
     group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   else
@@ -446,12 +494,15 @@ hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_
                           int group_size, int sel_size, int fmt, void* W_hat, int64_t ldo,
                           hipStream_t stream) {
   if (N == 0 || K == 0) return hipSuccess;
-  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  const unsigned gblocks = stream_blocks(N * (K / 8));
   uint16_t* out = static_cast<uint16_t*>(W_hat);
+  int gshift = 0, sshift = 0;
+  for (int g = group_size; g > 1; g >>= 1) ++gshift;
+  for (int g = sel_size; g > 1; g >>= 1) ++sshift;
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
 #define AAAC_DEQUANT(FMT, BITS)                                                                              \
-  dequant_kernel<FMT, BITS><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sel_size, tables_bf16, \
-                                                            N, K, group_size, out, ldo)
+  dequant_kernel<FMT, BITS><<<gblocks, kBlock, 0, stream>>>(codes, scales, bits, sel_stride, sshift, tables_bf16, \
+                                                            N, K, gshift, out, ldo)
   if (fmt == 0) {
     if (bits) AAAC_DEQUANT(0, true); else AAAC_DEQUANT(0, false);
   } else {
