@@ -281,13 +281,21 @@ __global__ __launch_bounds__(kLloydBlock) void lloyd_iter_kernel(const BatchArgs
   if (lane == 0) sm.red[wave] = obj;
   __syncthreads();
   double* acc = state->acc[iteration % 3][bid % kAccCopies];
-  if (tid < 64) {
-    const double* h = &sm.hist[0][0][0] + tid * kSlots;
+  // The kSlots copies of each of the 64 sums: 16 threads per sum, each adds kSlots / 16 neighbouring
+  // slots (consecutive lanes read consecutive addresses; one thread per sum walking its slots would
+  // put all 64 lanes on the same bank), then the 16 partial sums are added across the lanes.
+  {
+    static_assert(kLloydBlock == 64 * 16 && kSlots % 16 == 0, "16 threads per sum");
+    const int bin = tid >> 4, part = tid & 15;
+    const double* h = &sm.hist[0][0][0] + bin * kSlots + part * (kSlots / 16);
     double s = 0.0;
 #pragma unroll
-    for (int k = 0; k < kSlots; ++k) s += h[k];
-    device_add(acc + tid, s);
-  } else if (tid == 64) {
+    for (int k = 0; k < kSlots / 16; ++k) s += h[k];
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o);
+    if (part == 0) device_add(acc + bin, s);
+  }
+  if (tid == 64) {
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < kLloydWaves; ++w) s += sm.red[w];
