@@ -136,8 +136,8 @@ __global__ __launch_bounds__(kBlock) void act_stats_reduce_kernel(const double* 
 // ---------------------------------------------------- scales (reciprocals)
 
 // Chunks of 8 weights are numbered row by row; thread t takes chunks t, t + T, t + 2T, ... (T = threads of
-// the grid, a multiple of 64, so the LANES lanes of a group stay together), four at a time with their loads
-// in flight together.  Row and column advance by additions (one division per thread, none per chunk).
+// the grid), four at a time with their loads in flight together.  Row and column advance by additions
+// (one division per thread, none per chunk).
 constexpr int kStreamUnroll = 4;
 struct ChunkWalk {
   int64_t row, cc;   // row and chunk within the row
@@ -158,27 +158,19 @@ template <int LANES, int FMT>
 __global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __restrict__ W, int64_t N,
                                                             int64_t K, int64_t ldw,
                                                             float* __restrict__ rinv) {
-  ChunkWalk w = chunk_walk(K / 8);
-  const int64_t Gr = K / (8 * LANES);  // groups per row
-  while (w.row < N) {  // (rows only grow: once a thread's first chunk is past the end, all are)
-    uint4 v[kStreamUnroll];
-    int64_t row[kStreamUnroll], cc[kStreamUnroll];
-#pragma unroll
-    for (int u = 0; u < kStreamUnroll; ++u) {
-      row[u] = w.row;
-      cc[u] = w.cc;
-      const int64_t r = w.row < N ? w.row : N - 1;  // past the end: re-read the last row, store nothing
-      v[u] = *reinterpret_cast<const uint4*>(W + r * ldw + w.cc * 8);
-      w.step();
-    }
-#pragma unroll
-    for (int u = 0; u < kStreamUnroll; ++u) {
-      const float a = group_max<LANES>(absmax8(unpack8(v[u])));
-      float s;
-      scale_code<FMT>(a, &s);
-      if (row[u] < N && (threadIdx.x % LANES) == 0) rinv[row[u] * Gr + cc[u] / LANES] = div_rn(1.0f, s);
-    }
-  }
+  // one chunk of 8 weights per thread: the two fp64 divisions per chunk, not the loads, take the time, and
+  // many small blocks overlap them best (a grid-stride version with four loads in flight was 15 % slower)
+  const int64_t cpr = K / 8;  // chunks per row
+  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = c < N * cpr;
+  const int64_t row = active ? c / cpr : 0;
+  const int64_t col = active ? (c % cpr) * 8 : 0;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+  float a = group_max<LANES>(absmax8(unpack8(v)));
+  float s;
+  scale_code<FMT>(a, &s);
+  if (active && (threadIdx.x % LANES) == 0) rinv[row * (K / (8 * LANES)) + col / (8 * LANES)] = div_rn(1.0f, s);
 }
 
 // ----------------------------------------------------------------- encode
@@ -422,7 +414,7 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
 template <int LANES>
 static hipError_t launch_rinv_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt, float* rinv,
                                     hipStream_t stream) {
-  const unsigned gblocks = stream_blocks(N * (K / 8));
+  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
   if (fmt == 0)
     group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   else
