@@ -90,7 +90,10 @@ def importance_for(cfg, key):
 
 # ------------------------------------------------------------- importance
 
-@pytest.mark.parametrize("tokens,K,pad", [(256, 512, 0), (37, 520, 8), (1, 8, 0), (1000, 1032, 24), (4096, 4096, 0)])
+@pytest.mark.parametrize("tokens,K,pad", [(256, 512, 0), (37, 520, 8), (1, 8, 0), (1000, 1032, 24), (4096, 4096, 0),
+                                          (700, 28672, 0),     # 7 column groups of 4096
+                                          (5000, 11008, 0),    # 3 column groups x 85 token chunks, ragged last group
+                                          (300, 12000, 16)])
 def test_act_stats_matches_oracle(tokens, K, pad):
     say(f"[act_stats] tokens={tokens} K={K} pad={pad}")
     X = inputs.make_activations(tokens, K + pad, ("gauss", 3, "x20"), 7, DEV)[:, :K]
