@@ -193,9 +193,11 @@ int aaac_dequant_sel(const uint8_t* codes, const void* scales, const uint8_t* se
  * computed from the codes, scales (and selection bits) as aaac_encode / aaac_encode_sel
  * write them; the dequantised weights are never stored and w^ is the real product (no
  * bf16 rounding of it).  Arithmetic: fp32 accumulation of exact bf16 products, every term
- * exact; only the order of the additions differs from exact evaluation: at most 22 + 4 * ceil(K / 2048) roundings lie
- * on the path of a term, so |error| <= (22 + 4 * ceil(K / 2048)) * 2^-24 * sum_k |x w^|
- * to first order.
+ * exact; only the order of the additions differs from exact evaluation: at most
+ * 22 + 4 * ceil(K / 2048) roundings lie on the path of a term, so
+ * |error| <= (22 + 4 * ceil(K / 2048)) * 2^-24 * sum_k |x w^| to first order.  The additions
+ * across column slabs are LDS atomics whose order is not fixed: results may differ between
+ * runs in the last bits.
  * Meant for a few rows of x (decode); x is taken eight rows at a time, so larger M
  * re-reads the codes M/8 times.
  *   x        dev bf16 [M x ldx], ldx >= K, ldx % 8 == 0, 16-byte aligned
@@ -216,16 +218,16 @@ int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
  *   y[m, n] = sum_k x[m, k] * w^[n, k]
  * so the result is the fp32-accumulated product of x with the dequantised layer, without
  * that layer ever being written.  Small batches stream the codes once per 64 rows of x;
- * large ones use 128 x 128 / 128 x 256 tiles whose weights are dequantised once per tile.  Arguments and errors as aaac_gemv_w4a16, except K % 64 == 0,
- * scales 8-byte aligned, and
+ * large ones use 128 x 128 / 128 x 256 tiles whose weights are dequantised once per tile.
+ * Arguments and errors as aaac_gemv_w4a16, except K % 64 == 0, scales 8-byte aligned, and
  *   ws       dev scratch of aaac_gemm_w4a16_workspace(M, K) bytes, 256-byte aligned (x
  *            is first copied into the matrix instruction's operand order); too small or
  *            misaligned is AAAC_ERR_WORKSPACE. */
 size_t aaac_gemm_w4a16_workspace(int64_t M, int64_t K);
 int aaac_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes, const void* scales,
                     const uint8_t* sel_bits, int64_t sel_stride, const uint16_t* tables_bf16, int64_t N,
-                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy, void* ws,
-                    size_t ws_bytes, void* hip_stream);
+                    int64_t K, int group_size, int sel_size, aaac_format_t fmt, float* y, int64_t ldy,
+                    void* ws, size_t ws_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }
