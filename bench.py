@@ -221,37 +221,51 @@ def main():
         weights_per_s_iter = n_w / (iter_us * 1e-6)
 
     def time_product(Mx, matrix_cores):
-        # the quantised layers of the last step applied to Mx activation rows; 20 calls per layer
-        # are captured in a HIP graph so that the host's call overhead does not hide the kernel
+        # The quantised layers of the last step applied to Mx activation rows; 20 calls per layer are
+        # captured in a HIP graph so that the host's call overhead does not hide the kernel.  The calls
+        # cycle through copies of the layer that together exceed the 256 MB cache behind L2, so that
+        # `us` is the time with the codes coming from HBM, as in decoding, where a token reads every
+        # layer once; `us_cached` repeats one copy, which that cache then holds when it is small enough.
         side = torch.cuda.Stream()
         per_layer = []
         for L in layers:
             xs = torch.randn((Mx, L["K"]), device=dev).to(torch.bfloat16)
             ys = torch.empty((Mx, L["N"]), dtype=torch.float32, device=dev)
-            if matrix_cores:
-                wsx = torch.empty(max(A.aaac_gemm_w4a16_workspace(Mx, L["K"]), 256), dtype=torch.uint8, device=dev)
-                call = lambda st: A.aaac_gemm_w4a16(xs, L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt, y=ys,
-                                                    ws=wsx, stream=st)
-            else:
-                call = lambda st: A.aaac_gemv_w4a16(xs, L["codes"], L["scales"], L["bits"], L["tb"], g, S, fmt, y=ys,
-                                                    stream=st)
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                call(side)
-                torch.cuda.synchronize()
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph, stream=side):
-                    for _ in range(20):
-                        call(side)
-                graph.replay()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(side)
-                graph.replay()
-                e1.record(side)
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / 20
             nbytes = L["N"] * L["K"] * (0.5 + (1 if fmt == A.NVFP4 else 2) / g + (1 / (8 * S) if S < g else 0))
-            per_layer.append({"layer": L["name"], "us": us, "weights_per_s": L["N"] * L["K"] / (us * 1e-6),
+            ncopy = int(min(16, max(1, -(-600e6 // nbytes))))
+            copies = [(L["codes"], L["scales"], L["bits"])] + [
+                (L["codes"].clone(), L["scales"].clone(), None if L["bits"] is None else L["bits"].clone())
+                for _ in range(ncopy - 1)]
+            wsx = torch.empty(max(A.aaac_gemm_w4a16_workspace(Mx, L["K"]), 256), dtype=torch.uint8, device=dev) \
+                if matrix_cores else None
+
+            def call(st, c):
+                codes, scales, bits = copies[c % len(copies)]
+                if matrix_cores:
+                    A.aaac_gemm_w4a16(xs, codes, scales, bits, L["tb"], g, S, fmt, y=ys, ws=wsx, stream=st)
+                else:
+                    A.aaac_gemv_w4a16(xs, codes, scales, bits, L["tb"], g, S, fmt, y=ys, stream=st)
+
+            def timed(cycle):
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    call(side, 0)
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=side):
+                        for i in range(20):
+                            call(side, i if cycle else 0)
+                    graph.replay()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(side)
+                    graph.replay()
+                    e1.record(side)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) * 1e3 / 20
+            us, us_cached = timed(True), timed(False)
+            del copies
+            per_layer.append({"layer": L["name"], "us": us, "us_cached": us_cached, "copies_cycled": ncopy,
+                              "weights_per_s": L["N"] * L["K"] / (us * 1e-6),
                               "hbm_GBs": nbytes / (us * 1e-6) / 1e9, "hbm_frac": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                               "TFLOPs": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12,
                               "mfma_frac": 2.0 * Mx * L["N"] * L["K"] / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS})

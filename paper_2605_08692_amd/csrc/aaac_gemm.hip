@@ -111,9 +111,10 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   for (int i = tid; i < kGemmWaves * 16 * (MT * 16 + kTilePad); i += kGemmBlock) (&sm.y[0][0])[i] = 0.0f;
   __syncthreads();
-  for (int i = tid; i < 2 * 256 * kGemmReplicas; i += kGemmBlock) {
-    const int b = (i / kGemmReplicas) & 255, t = i / (256 * kGemmReplicas);
-    (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
+  for (int i = tid; i < 2 * 256 * kGemmReplicas / 2; i += kGemmBlock) {  // 16-byte stores of two copies each
+    const int b = (i / (kGemmReplicas / 2)) & 255, t = i / (256 * (kGemmReplicas / 2));
+    const float lo = sm.T[16 * t + (b & 15)], hi = sm.T[16 * t + (b >> 4)];
+    reinterpret_cast<float4*>(&sm.pair[0][0][0])[i] = make_float4(lo, hi, lo, hi);
   }
   __syncthreads();
 
@@ -288,9 +289,10 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   __syncthreads();
-  for (int i = tid; i < 2 * 256 * kTiledReplicas; i += kTiledBlock) {
-    const int b = (i / kTiledReplicas) & 255, t = i / (256 * kTiledReplicas);
-    (&sm.pair[0][0][0])[i] = make_float2(sm.T[16 * t + (b & 15)], sm.T[16 * t + (b >> 4)]);
+  for (int i = tid; i < 2 * 256 * kTiledReplicas / 2; i += kTiledBlock) {  // 16-byte stores of two copies each
+    const int b = (i / (kTiledReplicas / 2)) & 255, t = i / (256 * (kTiledReplicas / 2));
+    const float lo = sm.T[16 * t + (b & 15)], hi = sm.T[16 * t + (b >> 4)];
+    reinterpret_cast<float4*>(&sm.pair[0][0][0])[i] = make_float4(lo, hi, lo, hi);
   }
   __syncthreads();
 

@@ -101,9 +101,12 @@ __global__ __launch_bounds__(kGemvBlock) __attribute__((amdgpu_waves_per_eu(MB >
   if (tid < 32) sm.T[tid] = tables_bf16[tid];
   for (int i = tid; i < kGemvMaxRows * 8; i += kGemvBlock) (&sm.y[0][0])[i] = 0.0f;
   __syncthreads();
-  for (int i = tid; i < 2 * 256 * kPairReplicas; i += kGemvBlock) {
-    const int b = (i / kPairReplicas) & 255, t = i / (256 * kPairReplicas);
-    (&sm.pair[0][0][0])[i] = sm.T[16 * t + (b & 15)] | (sm.T[16 * t + (b >> 4)] << 16);
+  // 16-byte stores of four copies each (neighbouring threads write neighbouring 16 bytes): the table
+  // is 64 KB per block, and the block's loads start only after it
+  for (int i = tid; i < 2 * 256 * kPairReplicas / 4; i += kGemvBlock) {
+    const int b = (i / (kPairReplicas / 4)) & 255, t = i / (256 * (kPairReplicas / 4));
+    const uint32_t v = sm.T[16 * t + (b & 15)] | (sm.T[16 * t + (b >> 4)] << 16);
+    reinterpret_cast<uint4*>(&sm.pair[0][0][0])[i] = make_uint4(v, v, v, v);
   }
   __syncthreads();
 
