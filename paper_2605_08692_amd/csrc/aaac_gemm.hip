@@ -81,10 +81,14 @@ struct ChunkRegs {
 // the packed array is the 16-byte B operand of lane (r, q) for chunk c, step st, x tile j, i.e.
 // x[16 j + r][256 c + 64 q + 8 st .. + 7] (zero outside the matrix), so that a wavefront's operand
 // load is one contiguous kilobyte.
+// With clear_n > 0 the kernel also clears y[0 .. M)[0 .. clear_n) (for a product that adds its parts into y).
 template <int MT>
 __global__ void pack_x_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K, int chunks,
-                              uint4* __restrict__ xpack) {
+                              uint4* __restrict__ xpack, float* __restrict__ y = nullptr, int64_t ldy = 0,
+                              int clear_n = 0) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int64_t e = i; e < (int64_t)M * clear_n; e += (int64_t)gridDim.x * blockDim.x)
+    y[(e / clear_n) * ldy + e % clear_n] = 0.0f;
   if (i >= (int64_t)chunks * 8 * MT * 64) return;
   const int lane = (int)(i & 63), r = lane & 15, q = lane >> 4;
   const int64_t rest = i >> 6;
@@ -250,6 +254,189 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
   for (int i = tid; i < rows * MT * 16; i += kGemmBlock) {
     const int row = i % rows, m = i / rows;
     if (n_base + row < N && m < M) y[(int64_t)m * ldy + n_base + row] = sm.y[row][m];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Few rows of x (M <= 32, batched decoding): x stays in registers.  A block owns 64 layer rows; a
+// wavefront owns one 256-column chunk at a time (lane (r, q): columns 64q .. 64q + 63 of it), loads
+// the B operands of that chunk once, straight from row-major x (x[16 j + r][k0 + 8 st .. + 7] is 16
+// contiguous bytes), and walks down the block's four tiles of 16 layer rows: two 16-byte code loads
+// per lane and tile, dequantised into the A operand as in the streaming kernel, and 8 MT matrix
+// instructions into accumulators that stay in registers over all the wavefront's chunks.  At the end
+// every wavefront writes its 64 x 16 MT partial sums to a slab of its own in LDS (over the pair
+// table, which is no longer needed) and the block adds the 8 slabs while storing y.  Unlike the
+// streaming kernel, where every wavefront reads all of x through L1 (four times the bytes of the
+// codes at 16 rows), x is read once per 64 layer rows.
+constexpr int kRowsTile = 64;  // layer rows of a block
+constexpr int kRowsTiles = kRowsTile / 16;
+constexpr int kSlabPad = 4;  // a slab row is 16 MT + 4 floats: lanes (r, q) of one store fall into 64 banks
+
+template <int MT>
+struct alignas(16) RowsLds {
+  union {
+    float2 pair[2][256][kGemmReplicas];
+    float part[kGemmWaves][kRowsTile][MT * 16 + kSlabPad];
+  };
+  float T[32];
+};
+
+struct TileRegs {  // what a lane loads per tile of 16 layer rows: 32 code bytes, raw scale bytes, selection byte
+  uint4 c0, c1;
+  uint2 sc;
+  uint32_t selbyte;
+};
+
+template <int FMT, int MT, int GS, bool SEL>
+__global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_rows_kernel(
+    const uint4* __restrict__ xpack, int M, const uint8_t* __restrict__ codes,
+    const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
+    const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
+    int64_t ldy) {
+  __shared__ RowsLds<MT> sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
+  __syncthreads();
+
+  const int r = lane & 15, q = lane >> 4;
+  const int r0 = blockIdx.x * kRowsTile;
+  const int r1 = r0 + kRowsTile < N ? r0 + kRowsTile : N;
+  const int chunks = (K + kChunkCols - 1) / kChunkCols;
+  const int Gs = K >> gshift;
+  const int rep = lane & (kGemmReplicas - 1);
+  const int64_t row_bytes = K / 2;
+
+  // this lane's columns of chunk c: all 64 or none (K % 64 == 0); a lane beyond K reads the row's
+  // first columns and multiplies them with the zeros that the packed x holds there
+  auto lane_cols = [&](int c) { return c * kChunkCols + 64 * q; };
+  // loads are unconditional, from clamped addresses (a row beyond the block's last reads the last
+  // row; its sums are not stored)
+  auto fetch = [&](TileRegs& tr, int c, int t) {
+    const int k0 = lane_cols(c), kc = k0 < K ? k0 : 0;
+    const int n0 = r0 + 16 * t + r;
+    const int n = n0 < r1 ? n0 : r1 - 1;
+    const uint8_t* cp = codes + (int64_t)n * row_bytes + kc / 2;
+    tr.c0 = *reinterpret_cast<const uint4*>(cp);
+    tr.c1 = *reinterpret_cast<const uint4*>(cp + 16);
+    const int64_t g0 = (int64_t)n * Gs + (kc >> gshift);
+    tr.sc = make_uint2(0, 0);
+    if (FMT == 0) {
+      const uint8_t* sp = static_cast<const uint8_t*>(scales) + g0;
+      if (GS == 4) tr.sc.x = *reinterpret_cast<const uint32_t*>(sp);
+      else if (GS == 5) tr.sc.x = *reinterpret_cast<const uint16_t*>(sp);
+      else tr.sc.x = *sp;
+    } else {
+      const uint16_t* sp = static_cast<const uint16_t*>(scales) + g0;
+      if (GS == 4) tr.sc = *reinterpret_cast<const uint2*>(sp);
+      else if (GS == 5) tr.sc.x = *reinterpret_cast<const uint32_t*>(sp);
+      else tr.sc.x = *sp;
+    }
+    tr.selbyte = 0;
+    if (SEL) tr.selbyte = sel_bits[(int64_t)n * sel_stride + ((kc >> sshift) >> 3)];
+  };
+
+  f32x4 acc[kRowsTiles][MT];
+#pragma unroll
+  for (int t = 0; t < kRowsTiles; ++t)
+#pragma unroll
+    for (int j = 0; j < MT; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // blockIdx.y: which part of the chunk sequence this block sums (the parts are added in y)
+  const int c_begin = (int)((int64_t)chunks * blockIdx.y / gridDim.y);
+  const int c_end = (int)((int64_t)chunks * (blockIdx.y + 1) / gridDim.y);
+  // the first tile's codes travel while the pair table is built (a barrier waits for loads in flight,
+  // so they are asked for after the first one)
+  TileRegs cur, nxt;
+  fetch(cur, c_begin + wave < c_end ? c_begin + wave : c_end - 1, 0);
+  for (int i = tid; i < 2 * 256 * kGemmReplicas / 2; i += kGemmBlock) {  // 16-byte stores of two copies each
+    const int b = (i / (kGemmReplicas / 2)) & 255, t = i / (256 * (kGemmReplicas / 2));
+    const float lo = sm.T[16 * t + (b & 15)], hi = sm.T[16 * t + (b >> 4)];
+    reinterpret_cast<float4*>(&sm.pair[0][0][0])[i] = make_float4(lo, hi, lo, hi);
+  }
+  __syncthreads();
+  if (c_begin + wave < c_end) {
+    for (int c = c_begin + wave; c < c_end; c += kGemmWaves) {
+      const int k0 = lane_cols(c);
+      const bool active = k0 < K;
+      const int kc = active ? k0 : 0;
+      // the chunk's B operands, one contiguous kilobyte per step and x tile (zero beyond M and K)
+      uint4 xv[8][MT];
+#pragma unroll
+      for (int j = 0; j < MT; ++j)
+#pragma unroll
+        for (int st = 0; st < 8; ++st) xv[st][j] = xpack[((int64_t)(c * 8 + st) * MT + j) * 64 + lane];
+      const int c_next = c + kGemmWaves < c_end ? c + kGemmWaves : c;
+#pragma unroll
+      for (int t = 0; t < kRowsTiles; ++t) {
+        // the next tile's codes are on their way while this one is worked on
+        asm volatile("" ::: "memory");
+        if (t + 1 < kRowsTiles) fetch(nxt, c, t + 1);
+        else fetch(nxt, c_next, 0);
+        asm volatile("" ::: "memory");
+        float s_val[4];
+        uint32_t sigma[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {  // block b: columns k0 + 16 b .. + 15, scale number e of the lane's
+          constexpr int kW = FMT == 0 ? 8 : 16;
+          const int e = (16 * b) >> GS;
+          const uint32_t word = FMT == 1 && e >= 2 ? cur.sc.y : cur.sc.x;
+          const uint32_t code = (word >> (kW * (FMT == 1 ? e & 1 : e))) & (FMT == 0 ? 0xFFu : 0xFFFFu);
+          s_val[b] = gemm_scale_value<FMT>(code, &sigma[b]);
+          if (SEL) sigma[b] = (cur.selbyte >> (((kc + 16 * b) >> sshift) & 7)) & 1u;
+        }
+        // columns k0 + 8 st .. + 7 are four code bytes; their table entries are read one step ahead of
+        // the multiplications, so that LDS latency is not waited for byte by byte
+        auto lookup = [&](float2 (&p)[4], int st) {
+          const uint32_t cw = st < 4 ? (st == 0 ? cur.c0.x : st == 1 ? cur.c0.y : st == 2 ? cur.c0.z : cur.c0.w)
+                                     : (st == 4 ? cur.c1.x : st == 5 ? cur.c1.y : st == 6 ? cur.c1.z : cur.c1.w);
+          const float2* tab = &sm.pair[sigma[st / 2]][0][rep];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) p[i] = tab[((cw >> (8 * i)) & 0xFFu) * kGemmReplicas];
+        };
+        float2 pa[4], pb[4];
+        lookup(pa, 0);
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+          float2(&p)[4] = (st & 1) ? pb : pa;
+          float2(&pn)[4] = (st & 1) ? pa : pb;
+          if (st + 1 < 8) lookup(pn, st + 1);
+          const float sv = s_val[st / 2];
+          uint32_t a32[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) a32[i] = pack_bf16(p[i].x * sv, p[i].y * sv);
+          bf16x8 a;
+          __builtin_memcpy(&a, a32, 16);
+#pragma unroll
+          for (int j = 0; j < MT; ++j) {
+            bf16x8 bv;
+            __builtin_memcpy(&bv, &xv[st][j], 16);
+            acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[t][j], 0, 0, 0);
+          }
+        }
+        cur = nxt;
+      }
+    }
+  }
+  __syncthreads();  // every wavefront is done with the pair table
+  // this lane holds D[4q + e][r] of each tile: layer rows 16 t + 4q + e of the block, x row 16 j + r
+#pragma unroll
+  for (int t = 0; t < kRowsTiles; ++t)
+#pragma unroll
+    for (int j = 0; j < MT; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sm.part[wave][16 * t + 4 * q + e][16 * j + r] = acc[t][j][e];
+  __syncthreads();
+  const int rows = r1 - r0;
+  for (int i = tid; i < rows * MT * 16; i += kGemmBlock) {
+    const int row = i % rows, m = i / rows;
+    if (m < M) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kGemmWaves; ++w) sum += sm.part[w][row][m];
+      float* out = y + (int64_t)m * ldy + r0 + row;
+      if (gridDim.y == 1) *out = sum;
+      else atomicAdd(out, sum);  // y was cleared by the kernel that packed x
+    }
   }
 }
 
@@ -548,6 +735,55 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
       if (wide) AAAC_TILED(1, 256); else AAAC_TILED(1, 128);
     }
 #undef AAAC_TILED
+    return hipGetLastError();
+  }
+  if (M <= 32) {  // x in registers, one pass over the codes
+    const int gsh = log2i(group_size), ssh = log2i(sel_size);
+    const int chunks = (int)((K + kChunkCols - 1) / kChunkCols);
+    const int row_tiles = (int)((N + kRowsTile - 1) / kRowsTile);
+    // With few row tiles the chunk sequence is split over blockIdx.y and the parts are added into y,
+    // which the packing kernel clears: two blocks per compute unit if every wavefront still gets two
+    // chunks, else one (a block pays about 3 us for its table and the final sum), at least one chunk
+    // per wavefront.
+    int ksplit = (2 * cus + row_tiles / 2) / row_tiles;
+    if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
+      ksplit = (cus + row_tiles / 2) / row_tiles;
+      if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
+      if (ksplit < 1) ksplit = 1;
+    }
+    const int mt = M <= 16 ? 1 : 2;
+    uint4* xpk = static_cast<uint4*>(ws);
+    const int64_t items = (int64_t)chunks * 8 * mt * 64;
+    const unsigned pack_grid = (unsigned)((items + 255) / 256);
+    if (mt == 1)
+      pack_x_kernel<1><<<pack_grid, 256, 0, stream>>>(xp, ldx, (int)M, (int)K, chunks, xpk, y, ldy, ksplit > 1 ? (int)N : 0);
+    else
+      pack_x_kernel<2><<<pack_grid, 256, 0, stream>>>(xp, ldx, (int)M, (int)K, chunks, xpk, y, ldy, ksplit > 1 ? (int)N : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)row_tiles, (unsigned)ksplit);
+#define AAAC_ROWS(FMT, MT, GS, SEL)                                                                                \
+  gemm_w4a16_rows_kernel<FMT, MT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpk, (int)M, codes, scales, bits, sel_stride, \
+                                                                            tables_bf16, (int)N, (int)K, gsh, ssh, y, ldy)
+#define AAAC_ROWS_GS(FMT, MT, SEL)                    \
+  do {                                                \
+    if (gsh == 4) AAAC_ROWS(FMT, MT, 4, SEL);         \
+    else if (gsh == 5) AAAC_ROWS(FMT, MT, 5, SEL);    \
+    else AAAC_ROWS(FMT, MT, 6, SEL);                  \
+  } while (0)
+#define AAAC_ROWS_MT(FMT, SEL)                        \
+  do {                                                \
+    if (mt == 1) AAAC_ROWS_GS(FMT, 1, SEL);           \
+    else AAAC_ROWS_GS(FMT, 2, SEL);                   \
+  } while (0)
+    if (fmt == 0) {
+      if (bits != nullptr) AAAC_ROWS_MT(0, true); else AAAC_ROWS_MT(0, false);
+    } else {
+      if (bits != nullptr) AAAC_ROWS_MT(1, true); else AAAC_ROWS_MT(1, false);
+    }
+#undef AAAC_ROWS_MT
+#undef AAAC_ROWS_GS
+#undef AAAC_ROWS
     return hipGetLastError();
   }
   uint4* xpack = static_cast<uint4*>(ws);
