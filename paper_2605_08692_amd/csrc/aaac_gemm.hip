@@ -634,29 +634,15 @@ hipError_t launch_tiles(hipStream_t stream, const uint16_t* x, int64_t ldx, int 
   return hipGetLastError();
 }
 
-template <int FMT, int GS, bool SEL>
-hipError_t launch_mt(int mt, hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
-                     const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
-                     const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
-                     uint4* xpack, int cus) {
-  if (mt == 1)
-    return launch_tiles<FMT, 1, 1, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
-                                            gshift, sshift, y, ldy, xpack, cus);
-  if (mt == 2)
-    return launch_tiles<FMT, 2, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
-                                            gshift, sshift, y, ldy, xpack, cus);
-  return launch_tiles<FMT, 4, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K,
-                                          gshift, sshift, y, ldy, xpack, cus);
-}
-
-// the streaming kernel's template parameters from the run-time format, group size and selection mode
-hipError_t launch_streaming(int fmt, int gshift, bool sel, int mt, hipStream_t stream, const uint16_t* x, int64_t ldx,
-                            int M, const uint8_t* codes, const void* scales, const uint8_t* sel_bits,
-                            int64_t sel_stride, const uint16_t* tables_bf16, int N, int K, int sshift, float* y,
-                            int64_t ldy, uint4* xpack, int cus) {
-#define AAAC_STREAM(FMT, GS, SEL)                                                                                  \
-  return launch_mt<FMT, GS, SEL>(mt, stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, gshift, \
-                                 sshift, y, ldy, xpack, cus)
+// the streaming kernel (33 .. 64 rows of x: four x tiles, two layer-row tiles per wavefront) with its
+// template parameters taken from the run-time format, group size and selection mode
+hipError_t launch_streaming(int fmt, int gshift, bool sel, hipStream_t stream, const uint16_t* x, int64_t ldx, int M,
+                            const uint8_t* codes, const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
+                            const uint16_t* tables_bf16, int N, int K, int sshift, float* y, int64_t ldy,
+                            uint4* xpack, int cus) {
+#define AAAC_STREAM(FMT, GS, SEL)                                                                                    \
+  return launch_tiles<FMT, 4, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, \
+                                          gshift, sshift, y, ldy, xpack, cus)
 #define AAAC_STREAM_GS(FMT, SEL)                  \
   if (gshift == 4) AAAC_STREAM(FMT, 4, SEL);      \
   if (gshift == 5) AAAC_STREAM(FMT, 5, SEL);      \
@@ -669,6 +655,57 @@ hipError_t launch_streaming(int fmt, int gshift, bool sel, int mt, hipStream_t s
   AAAC_STREAM_GS(1, false);
 #undef AAAC_STREAM_GS
 #undef AAAC_STREAM
+}
+
+// the few-row kernel (M <= 32): x in registers, one pass over the codes
+hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uint16_t* xp, int64_t ldx, int M,
+                       const uint8_t* codes, const void* scales, const uint8_t* bits, int64_t sel_stride,
+                       const uint16_t* tables_bf16, int N, int K, int ssh, float* y, int64_t ldy, uint4* xpk,
+                       int cus) {
+  const int chunks = (K + kChunkCols - 1) / kChunkCols;
+  const int row_tiles = (N + kRowsTile - 1) / kRowsTile;
+  // With few row tiles the chunk sequence is split over blockIdx.y and the parts are added into y,
+  // which the packing kernel clears: two blocks per compute unit if every wavefront still gets two
+  // chunks, else one (a block pays about 3 us for its table and the final sum), at least one chunk
+  // per wavefront.
+  int ksplit = (2 * cus + row_tiles / 2) / row_tiles;
+  if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
+    ksplit = (cus + row_tiles / 2) / row_tiles;
+    if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
+    if (ksplit < 1) ksplit = 1;
+  }
+  const int mt = M <= 16 ? 1 : 2;
+  const int64_t items = (int64_t)chunks * 8 * mt * 64;
+  const unsigned pack_grid = (unsigned)((items + 255) / 256);
+  const int clear_n = ksplit > 1 ? N : 0;
+  if (mt == 1) pack_x_kernel<1><<<pack_grid, 256, 0, stream>>>(xp, ldx, M, K, chunks, xpk, y, ldy, clear_n);
+  else pack_x_kernel<2><<<pack_grid, 256, 0, stream>>>(xp, ldx, M, K, chunks, xpk, y, ldy, clear_n);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const dim3 grid((unsigned)row_tiles, (unsigned)ksplit);
+#define AAAC_ROWS(FMT, MT, GS, SEL)                                                                                  \
+  gemm_w4a16_rows_kernel<FMT, MT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpk, M, codes, scales, bits, sel_stride, \
+                                                                            tables_bf16, N, K, gsh, ssh, y, ldy)
+#define AAAC_ROWS_GS(FMT, MT, SEL)                    \
+  do {                                                \
+    if (gsh == 4) AAAC_ROWS(FMT, MT, 4, SEL);         \
+    else if (gsh == 5) AAAC_ROWS(FMT, MT, 5, SEL);    \
+    else AAAC_ROWS(FMT, MT, 6, SEL);                  \
+  } while (0)
+#define AAAC_ROWS_MT(FMT, SEL)                        \
+  do {                                                \
+    if (mt == 1) AAAC_ROWS_GS(FMT, 1, SEL);           \
+    else AAAC_ROWS_GS(FMT, 2, SEL);                   \
+  } while (0)
+  if (fmt == 0) {
+    if (sel) AAAC_ROWS_MT(0, true); else AAAC_ROWS_MT(0, false);
+  } else {
+    if (sel) AAAC_ROWS_MT(1, true); else AAAC_ROWS_MT(1, false);
+  }
+#undef AAAC_ROWS_MT
+#undef AAAC_ROWS_GS
+#undef AAAC_ROWS
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -737,62 +774,15 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
 #undef AAAC_TILED
     return hipGetLastError();
   }
-  if (M <= 32) {  // x in registers, one pass over the codes
-    const int gsh = log2i(group_size), ssh = log2i(sel_size);
-    const int chunks = (int)((K + kChunkCols - 1) / kChunkCols);
-    const int row_tiles = (int)((N + kRowsTile - 1) / kRowsTile);
-    // With few row tiles the chunk sequence is split over blockIdx.y and the parts are added into y,
-    // which the packing kernel clears: two blocks per compute unit if every wavefront still gets two
-    // chunks, else one (a block pays about 3 us for its table and the final sum), at least one chunk
-    // per wavefront.
-    int ksplit = (2 * cus + row_tiles / 2) / row_tiles;
-    if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
-      ksplit = (cus + row_tiles / 2) / row_tiles;
-      if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
-      if (ksplit < 1) ksplit = 1;
-    }
-    const int mt = M <= 16 ? 1 : 2;
-    uint4* xpk = static_cast<uint4*>(ws);
-    const int64_t items = (int64_t)chunks * 8 * mt * 64;
-    const unsigned pack_grid = (unsigned)((items + 255) / 256);
-    if (mt == 1)
-      pack_x_kernel<1><<<pack_grid, 256, 0, stream>>>(xp, ldx, (int)M, (int)K, chunks, xpk, y, ldy, ksplit > 1 ? (int)N : 0);
-    else
-      pack_x_kernel<2><<<pack_grid, 256, 0, stream>>>(xp, ldx, (int)M, (int)K, chunks, xpk, y, ldy, ksplit > 1 ? (int)N : 0);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)row_tiles, (unsigned)ksplit);
-#define AAAC_ROWS(FMT, MT, GS, SEL)                                                                                \
-  gemm_w4a16_rows_kernel<FMT, MT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpk, (int)M, codes, scales, bits, sel_stride, \
-                                                                            tables_bf16, (int)N, (int)K, gsh, ssh, y, ldy)
-#define AAAC_ROWS_GS(FMT, MT, SEL)                    \
-  do {                                                \
-    if (gsh == 4) AAAC_ROWS(FMT, MT, 4, SEL);         \
-    else if (gsh == 5) AAAC_ROWS(FMT, MT, 5, SEL);    \
-    else AAAC_ROWS(FMT, MT, 6, SEL);                  \
-  } while (0)
-#define AAAC_ROWS_MT(FMT, SEL)                        \
-  do {                                                \
-    if (mt == 1) AAAC_ROWS_GS(FMT, 1, SEL);           \
-    else AAAC_ROWS_GS(FMT, 2, SEL);                   \
-  } while (0)
-    if (fmt == 0) {
-      if (bits != nullptr) AAAC_ROWS_MT(0, true); else AAAC_ROWS_MT(0, false);
-    } else {
-      if (bits != nullptr) AAAC_ROWS_MT(1, true); else AAAC_ROWS_MT(1, false);
-    }
-#undef AAAC_ROWS_MT
-#undef AAAC_ROWS_GS
-#undef AAAC_ROWS
-    return hipGetLastError();
-  }
   uint4* xpack = static_cast<uint4*>(ws);
+  const int gsh = log2i(group_size), ssh = log2i(sel_size);
   for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time (the packed copy is reused)
     const int rows = (int)(M - m0 < 64 ? M - m0 : 64);
-    const int mt = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;
-    const hipError_t e = launch_streaming(fmt, log2i(group_size), bits != nullptr, mt, stream, xp + m0 * ldx, ldx, rows,
-                                          codes, scales, bits, sel_stride, tables_bf16, (int)N, (int)K,
-                                          log2i(sel_size), y + m0 * ldy, ldy, xpack, cus);
+    const hipError_t e =
+        rows <= 32 ? launch_rows(fmt, gsh, bits != nullptr, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits,
+                                 sel_stride, tables_bf16, (int)N, (int)K, ssh, y + m0 * ldy, ldy, xpack, cus)
+                   : launch_streaming(fmt, gsh, bits != nullptr, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits,
+                                      sel_stride, tables_bf16, (int)N, (int)K, ssh, y + m0 * ldy, ldy, xpack, cus);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
