@@ -76,29 +76,51 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
   int64_t row = e / cpr;
   int c = (int)(e - row * cpr);
   const int step_rows = kQBlock / cpr, step_c = kQBlock % cpr;
-  for (; e < end; e += kQBlock) {
-    const int col = c * 8;
-    const uint4 v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
-    const float r = rinv[row * Gs + (col >> gshift)];
-    const W8 w = unpack8(v);
+  // Four chunks are asked for together (a thread has few chunks, and waiting for each before asking
+  // for the next left the pass bound by memory latency); the loads are unconditional, a chunk beyond
+  // the block's range reads the batch's first chunk again and is not counted.
+  constexpr int kBatch = 4;
+  for (; e < end; e += kBatch * kQBlock) {
+    int64_t rows[kBatch];
+    int cs[kBatch];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const uint32_t key = order_key(w.w[p] * r);
-      if (PASS == 1) {
-        atomicAdd(&sm.hist[key >> 20], 1u);
-      } else {
-        uint32_t s = sm.map1[key >> 20];
-        if (PASS >= 3 && s != 0xFFu) s = sm.map2[s][(key >> 12) & 0xFFu];
-        if (PASS >= 4 && s != 0xFFu) s = sm.map3[s][(key >> 4) & 0xFFu];
-        if (s != 0xFFu) {
-          const uint32_t bin = (key >> PassBits<PASS>::shift) & (uint32_t)(PassBits<PASS>::bins - 1);
-          atomicAdd(&sm.hist[s * PassBits<PASS>::bins + bin], 1u);
+    for (int u = 0; u < kBatch; ++u) {
+      rows[u] = row;
+      cs[u] = c;
+      row += step_rows;
+      c += step_c;
+      if (c >= cpr) { c -= cpr; ++row; }
+    }
+    uint4 v[kBatch];
+    float r[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const bool ok = e + (int64_t)u * kQBlock < end;
+      const int64_t ru = ok ? rows[u] : rows[0];
+      const int col = (ok ? cs[u] : cs[0]) * 8;
+      v[u] = *reinterpret_cast<const uint4*>(W + ru * ldw + col);
+      r[u] = rinv[ru * Gs + (col >> gshift)];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (e + (int64_t)u * kQBlock >= end) break;
+      const W8 w = unpack8(v[u]);
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const uint32_t key = order_key(w.w[p] * r[u]);
+        if (PASS == 1) {
+          atomicAdd(&sm.hist[key >> 20], 1u);
+        } else {
+          uint32_t s = sm.map1[key >> 20];
+          if (PASS >= 3 && s != 0xFFu) s = sm.map2[s][(key >> 12) & 0xFFu];
+          if (PASS >= 4 && s != 0xFFu) s = sm.map3[s][(key >> 4) & 0xFFu];
+          if (s != 0xFFu) {
+            const uint32_t bin = (key >> PassBits<PASS>::shift) & (uint32_t)(PassBits<PASS>::bins - 1);
+            atomicAdd(&sm.hist[s * PassBits<PASS>::bins + bin], 1u);
+          }
         }
       }
     }
-    row += step_rows;
-    c += step_c;
-    if (c >= cpr) { c -= cpr; ++row; }
   }
   __syncthreads();
   unsigned long long* out = PASS == 1 ? qs->hist1 : &qs->hist[0][0];
