@@ -23,6 +23,11 @@
 // Two codes are dequantised with one LDS read (code byte -> fp32 pair of table
 // values), multiplied by the scale (exact: 8 x 8 significant bits) and rounded to
 // bf16 pairs by the hardware conversion.
+//
+// Three kernels share this mapping: gemm_w4a16_rows_kernel (up to 32 rows of x, which stay
+// in registers while a wavefront walks down the layer rows), gemm_w4a16_kernel (33 .. 64
+// rows: the streaming form described above) and gemm_w4a16_tiled_kernel (large batches:
+// weights dequantised once per tile into LDS).
 #include <cmath>
 
 #include "aaac_device.h"
