@@ -47,6 +47,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int MT>
 struct alignas(16) GemmLds {
@@ -469,8 +470,12 @@ struct alignas(16) TiledLds {
   float T[32];
 };
 
-template <int FMT, int BM>
-__global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
+// GS: log2 of the scale group size, 5 standing for 32 and more (one scale per 32 columns); SEL:
+// selection bits come from the bit array.  Both are template parameters so that every load of a stage
+// is unconditional: a load under a branch makes the compiler wait for all loads wherever it waits for one.
+template <int FMT, int BM, int GS, bool SEL>
+__global__ __launch_bounds__(kTiledBlock) __attribute__((amdgpu_waves_per_eu(BM == 256 ? 2 : 3, BM == 256 ? 2 : 3)))
+void gemm_w4a16_tiled_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int M, const uint8_t* __restrict__ codes,
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
@@ -495,7 +500,6 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
   const bool has_n = n < N;
   const int Gs = K >> gshift;
   const int rep = lane & (kTiledReplicas - 1);
-  const uint8_t* crow = codes + (int64_t)(has_n ? n : 0) * (K / 2);
   // multiplier role: quarter of the block tile
   const int r = lane & 15, q = lane >> 4;
   const int wn = (wave >> 1) * 64, wm = (wave & 1) * (BM / 2);
@@ -506,50 +510,43 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
 #pragma unroll
     for (int j = 0; j < kMJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // what a thread loads per stage: 16 code bytes, their scale codes and selection byte, 32 activations
-  // of one or two x rows
+  // What a thread loads per stage: 16 code bytes, the raw scale codes (taken apart where they are used) and
+  // selection byte, 32 activations of one or two x rows.  The loads are unconditional, from clamped
+  // addresses: a layer row beyond N reads row N - 1 and an x row beyond M reads row M - 1 (their outputs
+  // are not stored), the stage after the last reads the last stage again (never used).
   struct StageRegs {
     uint4 cw4;
-    uint32_t sc0, sc1, selbyte;
-    uint4 xv[kXRows][4];
+    uint32_t sc, selbyte;
+    u32x4 xv[kXRows * 4];
   };
+  const int n_load = has_n ? n : N - 1;
+  const uint8_t* crow_load = codes + (int64_t)n_load * (K / 2);
+  const uint16_t* xrow[kXRows];
+#pragma unroll
+  for (int xr = 0; xr < kXRows; ++xr) {
+    const int m = m_base + lrow + 128 * xr;
+    xrow[xr] = x + (int64_t)(m < M ? m : M - 1) * ldx;
+  }
   auto fetch = [&](StageRegs& sr, int k_stage) {
-    const int k0 = k_stage + 32 * half;
-    uint4 cw4 = make_uint4(0, 0, 0, 0);
-    uint32_t sc0 = 0, sc1 = 0, selbyte = 0;
-    if (has_n && k_stage < K) {
-      cw4 = *reinterpret_cast<const uint4*>(crow + k0 / 2);
-      const int64_t g0 = (int64_t)n * Gs + (k0 >> gshift);
-      if (gshift == 4) {
-        if (FMT == 0) {
-          const uint32_t v = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0);
-          sc0 = v & 0xFFu; sc1 = v >> 8;
-        } else {
-          const uint32_t v = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
-          sc0 = v & 0xFFFFu; sc1 = v >> 16;
-        }
-      } else {
-        sc0 = sc1 = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
-                             : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
-      }
-      if (sel_bits != nullptr) selbyte = sel_bits[(int64_t)n * sel_stride + ((k0 >> sshift) >> 3)];
-    }
-    sr.cw4 = cw4;
-    sr.sc0 = sc0;
-    sr.sc1 = sc1;
-    sr.selbyte = selbyte;
+    const int k0 = (k_stage < K ? k_stage : K - kTileK) + 32 * half;
+    sr.cw4 = *reinterpret_cast<const uint4*>(crow_load + k0 / 2);
+    const int64_t g0 = (int64_t)n_load * Gs + (k0 >> gshift);
+    if (GS == 4)
+      sr.sc = FMT == 0 ? (uint32_t) * reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g0)
+                       : *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(scales) + g0);
+    else
+      sr.sc = FMT == 0 ? (uint32_t) static_cast<const uint8_t*>(scales)[g0]
+                       : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
+    sr.selbyte = 0;
+    if (SEL) sr.selbyte = sel_bits[(int64_t)n_load * sel_stride + ((k0 >> sshift) >> 3)];
 #pragma unroll
-    for (int xr = 0; xr < kXRows; ++xr) {
-      const int m = m_base + lrow + 128 * xr;
+    for (int xr = 0; xr < kXRows; ++xr)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        sr.xv[xr][u] = make_uint4(0, 0, 0, 0);
-        if (m < M && k_stage < K) sr.xv[xr][u] = *reinterpret_cast<const uint4*>(x + (int64_t)m * ldx + k0 + 8 * u);
-      }
-    }
+      for (int u = 0; u < 4; ++u) sr.xv[4 * xr + u] = *reinterpret_cast<const u32x4*>(xrow[xr] + k0 + 8 * u);
   };
   StageRegs sr;
   fetch(sr, 0);
+  __builtin_assume(K >= kTileK);  // checked by the host
   for (int k_stage = 0; k_stage < K; k_stage += kTileK) {
     const int k0 = k_stage + 32 * half;
     // dequantise the 32 weights: two 16-column blocks with their scale and selection
@@ -557,9 +554,11 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
 #pragma unroll
     for (int u = 0; u < 4; ++u) {  // unit u: columns k0 + 8u .. k0 + 8u + 7
       const int blk = u / 2;
+      constexpr uint32_t kScaleMask = FMT == 0 ? 0xFFu : 0xFFFFu;
+      const uint32_t sc = GS == 4 ? (sr.sc >> (blk * (FMT == 0 ? 8 : 16))) & kScaleMask : sr.sc;
       uint32_t sigma;
-      const float s_val = gemm_scale_value<FMT>(blk == 0 ? sr.sc0 : sr.sc1, &sigma);
-      if (sel_bits != nullptr) sigma = (sr.selbyte >> (((k0 + 16 * blk) >> sshift) & 7)) & 1u;
+      const float s_val = gemm_scale_value<FMT>(sc, &sigma);
+      if (SEL) sigma = (sr.selbyte >> (((k0 + 16 * blk) >> sshift) & 7)) & 1u;
       const float2* tab = &sm.pair[sigma][0][rep];
       uint32_t a32[4];
 #pragma unroll
@@ -571,30 +570,40 @@ __global__ __launch_bounds__(kTiledBlock) void gemm_w4a16_tiled_kernel(
       const int unit = (4 * half + u) ^ (lrow & 7);
       sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
 #pragma unroll
-      for (int xr = 0; xr < kXRows; ++xr) sm.b[lrow + 128 * xr][unit] = sr.xv[xr][u];  // 128 keeps row & 7
+      for (int xr = 0; xr < kXRows; ++xr) *reinterpret_cast<u32x4*>(&sm.b[lrow + 128 * xr][unit]) = sr.xv[4 * xr + u];  // 128 keeps row & 7
     }
     __syncthreads();
-    fetch(sr, k_stage + kTileK);  // the next stage's loads are in flight during the matrix instructions
+    // the next stage's loads are in flight during the matrix instructions (the empty statements keep the
+    // compiler from moving them below)
+    asm volatile("" ::: "memory");
+    fetch(sr, k_stage + kTileK);
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 af[4], bfv[kMJ];
+      // the four A operands stay in registers; the B operands come one x tile at a time, the next one
+      // read from LDS while the current one's four matrix instructions run
+      bf16x8 af[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = wn + 16 * i + r;
         const uint4 v = sm.a[row][(4 * ks + q) ^ (row & 7)];
         __builtin_memcpy(&af[i], &v, 16);
       }
+      auto b_operand = [&](int j) {
+        const int row = wm + 16 * j + r;
+        return sm.b[row][(4 * ks + q) ^ (row & 7)];
+      };
+      uint4 b_cur = b_operand(0);
 #pragma unroll
       for (int j = 0; j < kMJ; ++j) {
-        const int row = wm + 16 * j + r;
-        const uint4 v = sm.b[row][(4 * ks + q) ^ (row & 7)];
-        __builtin_memcpy(&bfv[j], &v, 16);
+        uint4 b_next = b_cur;
+        if (j + 1 < kMJ) b_next = b_operand(j + 1);
+        bf16x8 bv;
+        __builtin_memcpy(&bv, &b_cur, 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bv, acc[i][j], 0, 0, 0);
+        b_cur = b_next;
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < kMJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfv[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
@@ -767,15 +776,27 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
     const bool wide = wide_us < narrow_us;
     const int bm = wide ? 256 : 128;
     const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm));
-#define AAAC_TILED(FMT, BM)                                                                                      \
-  gemm_w4a16_tiled_kernel<FMT, BM><<<grid, kTiledBlock, 0, stream>>>(xp, ldx, (int)M, codes, scales, bits, sel_stride, \
-                                                                     tables_bf16, (int)N, (int)K, log2i(group_size),  \
-                                                                     log2i(sel_size), y, ldy)
+#define AAAC_TILED(FMT, BM, GS, SEL)                                                                              \
+  gemm_w4a16_tiled_kernel<FMT, BM, GS, SEL><<<grid, kTiledBlock, 0, stream>>>(                                     \
+      xp, ldx, (int)M, codes, scales, bits, sel_stride, tables_bf16, (int)N, (int)K, log2i(group_size),          \
+      log2i(sel_size), y, ldy)
+#define AAAC_TILED_SEL(FMT, BM, GS)                                   \
+  do {                                                                \
+    if (bits != nullptr) AAAC_TILED(FMT, BM, GS, true);               \
+    else AAAC_TILED(FMT, BM, GS, false);                              \
+  } while (0)
+#define AAAC_TILED_GS(FMT, BM)                                        \
+  do {                                                                \
+    if (group_size == 16) AAAC_TILED_SEL(FMT, BM, 4);                 \
+    else AAAC_TILED_SEL(FMT, BM, 5);                                  \
+  } while (0)
     if (fmt == 0) {
-      if (wide) AAAC_TILED(0, 256); else AAAC_TILED(0, 128);
+      if (wide) AAAC_TILED_GS(0, 256); else AAAC_TILED_GS(0, 128);
     } else {
-      if (wide) AAAC_TILED(1, 256); else AAAC_TILED(1, 128);
+      if (wide) AAAC_TILED_GS(1, 256); else AAAC_TILED_GS(1, 128);
     }
+#undef AAAC_TILED_GS
+#undef AAAC_TILED_SEL
 #undef AAAC_TILED
     return hipGetLastError();
   }
