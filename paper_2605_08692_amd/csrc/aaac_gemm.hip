@@ -12,22 +12,15 @@
 // takes the 64 consecutive columns 64q..64q+63 of its row (two 16-byte code loads: the
 // four lanes of a row read one 128-byte line) and feeds them in eight steps of 8;
 // the lane that holds x row r takes the same columns of x (a small kernel first copies x
-// into that order, so that an operand load is one contiguous kilobyte).  A wavefront owns NT tiles of
-// 16 layer rows, so a loaded x operand feeds NT matrix instructions; the codes of the
-// next chunk are loaded while the current one is worked on.  A block of 8 wavefronts is
-// NSW wavefronts side by side along the rows x 8/NSW slices of the chunk sequence (NSW
-// chosen by the host: many rows -> wide blocks whose wavefronts read the same x at the
-// same time and share it in the L1 cache; few rows -> more slices of K), reduced
-// through a tile in LDS.
+// into that order, so that an operand load is one contiguous kilobyte).
 //
 // Two codes are dequantised with one LDS read (code byte -> fp32 pair of table
 // values), multiplied by the scale (exact: 8 x 8 significant bits) and rounded to
 // bf16 pairs by the hardware conversion.
 //
-// Three kernels share this mapping: gemm_w4a16_rows_kernel (up to 32 rows of x, which stay
-// in registers while a wavefront walks down the layer rows), gemm_w4a16_kernel (33 .. 64
-// rows: the streaming form described above) and gemm_w4a16_tiled_kernel (large batches:
-// weights dequantised once per tile into LDS).
+// Two kernels: gemm_w4a16_rows_kernel (up to 32 rows of x at a time, which stay in registers
+// while a wavefront walks down the layer rows; the mapping above) and gemm_w4a16_tiled_kernel
+// (large batches: weights dequantised once per 128 x 64 tile into LDS).
 #include <cmath>
 
 #include "aaac_device.h"
@@ -41,20 +34,12 @@ constexpr int kGemmBlock = 512;
 constexpr int kGemmWaves = kGemmBlock / 64;
 constexpr int kChunkCols = 256;      // columns per wavefront step: 4 lane quarters x 64
 constexpr int kGemmReplicas = 8;     // copies of the pair table
-constexpr int kTilePad = 1;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-template <int MT>
-struct alignas(16) GemmLds {
-  float2 pair[2][256][kGemmReplicas];              // [sigma][code byte][replica] = (T[b & 15], T[b >> 4])
-  float y[kGemmWaves * 16][MT * 16 + kTilePad];    // the block's output tile
-  float T[32];
-};
 
 template <int FMT>
 __device__ __forceinline__ float gemm_scale_value(uint32_t code, uint32_t* sign) {
@@ -74,14 +59,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   __builtin_memcpy(&u, &b, 4);
   return u;
 }
-
-// What a lane loads per 256-column chunk for one of its layer rows: 32 code bytes (its 64
-// columns), the scale codes of the four 16-column blocks, the byte with their selection bits.
-struct ChunkRegs {
-  uint4 c0, c1;
-  uint2 sc;  // the raw scale bytes, taken apart where they are used
-  uint32_t selbyte;
-};
 
 // x in the order the matrix instruction wants it: element ((c * 8 + st) * MT + j) * 64 + lane of
 // the packed array is the 16-byte B operand of lane (r, q) for chunk c, step st, x tile j, i.e.
@@ -105,175 +82,15 @@ __global__ void pack_x_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M
   xpack[i] = v;
 }
 
-// MT: tiles of 16 rows of x held at once (M <= 16 * MT in this launch); NT: tiles of 16 layer
-// rows per wavefront (each loaded x operand feeds NT matrix instructions); GS: log2 of the scale
-// group size, 6 standing for 64 and more (one scale per lane and chunk); SEL: selection bits come
-// from the bit array; NSW: wavefronts of the block that stand side by side along the rows (the
-// other 8 / NSW slice the chunks).
-template <int FMT, int MT, int NT, int GS, bool SEL>
-__global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_kernel(
-    const uint4* __restrict__ xpack, int M, const uint8_t* __restrict__ codes,
-    const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
-    const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
-    int64_t ldy, int NSW) {
-  __shared__ GemmLds<MT> sm;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
-  for (int i = tid; i < kGemmWaves * 16 * (MT * 16 + kTilePad); i += kGemmBlock) (&sm.y[0][0])[i] = 0.0f;
-  __syncthreads();
-  for (int i = tid; i < 2 * 256 * kGemmReplicas / 2; i += kGemmBlock) {  // 16-byte stores of two copies each
-    const int b = (i / (kGemmReplicas / 2)) & 255, t = i / (256 * (kGemmReplicas / 2));
-    const float lo = sm.T[16 * t + (b & 15)], hi = sm.T[16 * t + (b >> 4)];
-    reinterpret_cast<float4*>(&sm.pair[0][0][0])[i] = make_float4(lo, hi, lo, hi);
-  }
-  __syncthreads();
-
-  const int r = lane & 15, q = lane >> 4;
-  const int KS = kGemmWaves / NSW;           // slices of the chunk sequence
-  const int side = wave % NSW, slice = wave / NSW;
-  const int n_base = blockIdx.x * 16 * NT * NSW;
-  const int row0 = side * 16 * NT;           // first row of this wavefront inside the block's tile
-  const int Gs = K >> gshift;
-  const int rep = lane & (kGemmReplicas - 1);
-  const int64_t row_bytes = K / 2;
-  const int chunks = (K + kChunkCols - 1) / kChunkCols;
-
-  f32x4 acc[NT][MT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int j = 0; j < MT; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // Loads are unconditional, from clamped addresses, and their values are not touched here: a load
-  // under a branch makes the number of loads in flight unknown to the compiler, which then waits for
-  // all of them wherever it waits for one.  A row beyond N reads row N - 1 (its outputs are not
-  // stored), a chunk beyond the last reads chunk 0 (not used), columns beyond K read the row's first
-  // bytes (their x operand is zero).
-  auto fetch = [&](ChunkRegs (&cr)[NT], int c) {
-    const int k0 = c * kChunkCols + 64 * q;  // this lane's 64 columns (K % 64 == 0: all 64 or none)
-    const int kc = c < chunks && k0 < K ? k0 : 0;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int n0 = n_base + row0 + 16 * t + r;
-      const int n = n0 < N ? n0 : N - 1;
-      const uint8_t* cp = codes + (int64_t)n * row_bytes + kc / 2;
-      cr[t].c0 = *reinterpret_cast<const uint4*>(cp);
-      cr[t].c1 = *reinterpret_cast<const uint4*>(cp + 16);
-      const int64_t g0 = (int64_t)n * Gs + (kc >> gshift);
-      cr[t].sc = make_uint2(0, 0);
-      if (FMT == 0) {  // 4, 2 or 1 scale bytes for the lane's 64 columns
-        const uint8_t* sp = static_cast<const uint8_t*>(scales) + g0;
-        if (GS == 4) cr[t].sc.x = *reinterpret_cast<const uint32_t*>(sp);
-        else if (GS == 5) cr[t].sc.x = *reinterpret_cast<const uint16_t*>(sp);
-        else cr[t].sc.x = *sp;
-      } else {
-        const uint16_t* sp = static_cast<const uint16_t*>(scales) + g0;
-        if (GS == 4) cr[t].sc = *reinterpret_cast<const uint2*>(sp);
-        else if (GS == 5) cr[t].sc.x = *reinterpret_cast<const uint32_t*>(sp);
-        else cr[t].sc.x = *sp;
-      }
-      cr[t].selbyte = 0;
-      if (SEL) cr[t].selbyte = sel_bits[(int64_t)n * sel_stride + ((kc >> sshift) >> 3)];
-    }
-  };
-  // The chunk after this one is asked for (into `next`) right after this chunk's last x operands:
-  // loads complete in order, so a wait for the x operands also waits for whatever was asked for
-  // before them, and leaves in flight what was asked for after them.
-  auto work = [&](const ChunkRegs (&cr)[NT], ChunkRegs (&next)[NT], int c, int c_next) {
-    const int k0 = c * kChunkCols + 64 * q;
-    const uint4* xc = xpack + (int64_t)c * 8 * MT * 64 + lane;
-    float s_val[NT][4];
-    uint32_t sigma[NT][4];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {  // block b: columns k0 + 16 b .. + 15, scale number e of the lane's
-        constexpr int kW = FMT == 0 ? 8 : 16;
-        const int e = (16 * b) >> GS;
-        const uint32_t word = FMT == 1 && e >= 2 ? cr[t].sc.y : cr[t].sc.x;
-        const uint32_t code = (word >> (kW * (FMT == 1 ? e & 1 : e))) & (FMT == 0 ? 0xFFu : 0xFFFFu);
-        s_val[t][b] = gemm_scale_value<FMT>(code, &sigma[t][b]);
-        if (SEL) sigma[t][b] = (cr[t].selbyte >> (((k0 + 16 * b) >> sshift) & 7)) & 1u;
-      }
-    // the x operands of several steps are loaded together, ahead of the dequantisation that needs
-    // no memory: eight steps at a time while they fit the registers, else four
-    constexpr int kPhase = MT <= 2 ? 8 : 4;
-#pragma unroll
-    for (int ph = 0; ph < 8 / kPhase; ++ph) {
-      uint4 xv[kPhase][MT];
-#pragma unroll
-      for (int u = 0; u < kPhase; ++u)
-#pragma unroll
-        for (int j = 0; j < MT; ++j) xv[u][j] = xc[((ph * kPhase + u) * MT + j) * 64];
-      if (ph == 8 / kPhase - 1) {
-        // (the two empty statements keep the compiler from moving these loads: ahead of the x operands,
-        // or down to their first use in the next chunk)
-        asm volatile("" ::: "memory");
-        fetch(next, c_next);
-        asm volatile("" ::: "memory");
-      }
-#pragma unroll
-      for (int u = 0; u < kPhase; ++u) {  // columns k0 + 8 st .. k0 + 8 st + 7: four code bytes per row
-        const int st = ph * kPhase + u;
-        const int b = st / 2;
-        bf16x8 bv[MT];
-#pragma unroll
-        for (int j = 0; j < MT; ++j) __builtin_memcpy(&bv[j], &xv[u][j], 16);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const uint32_t cw = st < 4 ? (st == 0 ? cr[t].c0.x : st == 1 ? cr[t].c0.y : st == 2 ? cr[t].c0.z : cr[t].c0.w)
-                                     : (st == 4 ? cr[t].c1.x : st == 5 ? cr[t].c1.y : st == 6 ? cr[t].c1.z : cr[t].c1.w);
-          const float2* tab = &sm.pair[sigma[t][b]][0][rep];
-          uint32_t a32[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const uint32_t byte = (cw >> (8 * i)) & 0xFFu;
-            const float2 p = tab[byte * kGemmReplicas];
-            a32[i] = pack_bf16(p.x * s_val[t][b], p.y * s_val[t][b]);
-          }
-          bf16x8 a;
-          __builtin_memcpy(&a, a32, 16);
-#pragma unroll
-          for (int j = 0; j < MT; ++j)
-            acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv[j], acc[t][j], 0, 0, 0);
-        }
-      }
-    }
-  };
-  // the codes of the next chunk are on their way while this one is worked on
-  ChunkRegs cur[NT], nxt[NT];
-  fetch(cur, slice);
-  for (int c = slice; c < chunks; c += KS) {
-    work(cur, nxt, c, c + KS);
-#pragma unroll
-    for (int t = 0; t < NT; ++t) cur[t] = nxt[t];
-  }
-  // this lane holds D[4q + e][r] of each tile: layer rows row0 + 16 t + 4q + e, x row 16 j + r
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int j = 0; j < MT; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) atomicAdd(&sm.y[row0 + 16 * t + 4 * q + e][16 * j + r], acc[t][j][e]);
-  __syncthreads();
-  const int rows = NSW * NT * 16;
-  for (int i = tid; i < rows * MT * 16; i += kGemmBlock) {
-    const int row = i % rows, m = i / rows;
-    if (n_base + row < N && m < M) y[(int64_t)m * ldy + n_base + row] = sm.y[row][m];
-  }
-}
-
 // ---------------------------------------------------------------------------------
-// Few rows of x (M <= 32, batched decoding): x stays in registers.  A block owns 64 layer rows; a
+// Up to 32 rows of x (batched decoding): x stays in registers.  A block owns 64 layer rows; a
 // wavefront owns one 256-column chunk at a time (lane (r, q): columns 64q .. 64q + 63 of it), loads
-// the B operands of that chunk once, straight from row-major x (x[16 j + r][k0 + 8 st .. + 7] is 16
-// contiguous bytes), and walks down the block's four tiles of 16 layer rows: two 16-byte code loads
-// per lane and tile, dequantised into the A operand as in the streaming kernel, and 8 MT matrix
-// instructions into accumulators that stay in registers over all the wavefront's chunks.  At the end
-// every wavefront writes its 64 x 16 MT partial sums to a slab of its own in LDS (over the pair
-// table, which is no longer needed) and the block adds the 8 slabs while storing y.  Unlike the
-// streaming kernel, where every wavefront reads all of x through L1 (four times the bytes of the
-// codes at 16 rows), x is read once per 64 layer rows.
+// the B operands of that chunk once, from the packed copy of x, and walks down the block's four
+// tiles of 16 layer rows: two 16-byte code loads per lane and tile, dequantised into the A operand,
+// and 8 MT matrix instructions into accumulators that stay in registers over all the wavefront's
+// chunks.  At the end every wavefront writes its 64 x 16 MT partial sums to a slab of its own in
+// LDS (over the pair table, which is no longer needed) and the block adds the 8 slabs while
+// storing y.  x is read once per 64 layer rows and the codes once per 32 rows of x.
 constexpr int kRowsTile = 64;  // layer rows of a block
 constexpr int kRowsTiles = kRowsTile / 16;
 constexpr int kSlabPad = 4;  // a slab row is 16 MT + 4 floats: lanes (r, q) of one store fall into 64 banks
@@ -628,49 +445,6 @@ int log2i(int v) {
   return s;
 }
 
-template <int FMT, int MT, int NT, int GS, bool SEL>
-hipError_t launch_tiles(hipStream_t stream, const uint16_t* x, int64_t ldx, int M, const uint8_t* codes,
-                        const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
-                        const uint16_t* tables_bf16, int N, int K, int gshift, int sshift, float* y, int64_t ldy,
-                        uint4* xpack, int cus) {
-  const int chunks = (K + kChunkCols - 1) / kChunkCols;
-  const int64_t items = (int64_t)chunks * 8 * MT * 64;
-  pack_x_kernel<MT><<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(x, ldx, M, K, chunks, xpack);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  // wavefronts side by side along the rows: as many as still leave a block for every compute unit,
-  // at most 8 / NT (the block's tile in LDS holds 128 rows)
-  int nsw = kGemmWaves / NT;
-  while (nsw > 1 && (N + 16 * NT * nsw - 1) / (16 * NT * nsw) < cus) nsw /= 2;
-  const unsigned grid = (unsigned)((N + 16 * NT * nsw - 1) / (16 * NT * nsw));
-  gemm_w4a16_kernel<FMT, MT, NT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpack, M, codes, scales, sel_bits, sel_stride,
-                                                                 tables_bf16, N, K, gshift, sshift, y, ldy, nsw);
-  return hipGetLastError();
-}
-
-// the streaming kernel (33 .. 64 rows of x: four x tiles, two layer-row tiles per wavefront) with its
-// template parameters taken from the run-time format, group size and selection mode
-hipError_t launch_streaming(int fmt, int gshift, bool sel, hipStream_t stream, const uint16_t* x, int64_t ldx, int M,
-                            const uint8_t* codes, const void* scales, const uint8_t* sel_bits, int64_t sel_stride,
-                            const uint16_t* tables_bf16, int N, int K, int sshift, float* y, int64_t ldy,
-                            uint4* xpack, int cus) {
-#define AAAC_STREAM(FMT, GS, SEL)                                                                                    \
-  return launch_tiles<FMT, 4, 2, GS, SEL>(stream, x, ldx, M, codes, scales, sel_bits, sel_stride, tables_bf16, N, K, \
-                                          gshift, sshift, y, ldy, xpack, cus)
-#define AAAC_STREAM_GS(FMT, SEL)                  \
-  if (gshift == 4) AAAC_STREAM(FMT, 4, SEL);      \
-  if (gshift == 5) AAAC_STREAM(FMT, 5, SEL);      \
-  AAAC_STREAM(FMT, 6, SEL)
-  if (fmt == 0) {
-    if (sel) { AAAC_STREAM_GS(0, true); }
-    AAAC_STREAM_GS(0, false);
-  }
-  if (sel) { AAAC_STREAM_GS(1, true); }
-  AAAC_STREAM_GS(1, false);
-#undef AAAC_STREAM_GS
-#undef AAAC_STREAM
-}
-
 // the few-row kernel (M <= 32): x in registers, one pass over the codes
 hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uint16_t* xp, int64_t ldx, int M,
                        const uint8_t* codes, const void* scales, const uint8_t* bits, int64_t sel_stride,
@@ -754,12 +528,12 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
   // Large batches take the tiled kernel, which pays the dequantisation once per 128 or 256 rows of x
-  // but walks all of K inside one block; small ones take the streaming kernel, 64 rows of x per
-  // pass over the codes.  The choice compares cost models fitted to measurements on MI355X.
+  // but walks all of K inside one block; small ones take the few-row kernel, 32 rows of x per pass
+  // over the codes.  The choice compares cost models fitted to measurements on MI355X.
   // Tiled: a stage of 64 columns takes a block 1.33 us when it has the compute unit to itself and
   // 1.95 / 2.6 us when two / three blocks share it (128 rows of x; three fit), 2.0 / 3.0 us for one /
   // two blocks of 256 rows; the blocks run in rounds of (compute units x blocks that fit).
-  // Streaming: per pass 30 us + 0.4 ps per weight.
+  // Few rows: per pass 9 us + 0.2 ps per weight.
   const double work = (double)N * (double)K;
   const int64_t n_tiles = (N + kTileN - 1) / kTileN;
   const auto tiled_us = [&](int bm, const double* per_stage, int fit) {
@@ -771,8 +545,8 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   };
   static const double kNarrowStage[3] = {1.33, 1.95, 2.6}, kWideStage[2] = {2.0, 3.0};
   const double narrow_us = tiled_us(128, kNarrowStage, 3), wide_us = tiled_us(256, kWideStage, 2);
-  const double stream_us = (double)((M + 63) / 64) * (30.0 + 0.4e-6 * work);
-  if (M > 64 && (narrow_us < stream_us || wide_us < stream_us)) {
+  const double rows_us = (double)((M + 31) / 32) * (9.0 + 0.2e-6 * work);
+  if (M > 64 && (narrow_us < rows_us || wide_us < rows_us)) {
     const bool wide = wide_us < narrow_us;
     const int bm = wide ? 256 : 128;
     const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm));
@@ -802,13 +576,10 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   }
   uint4* xpack = static_cast<uint4*>(ws);
   const int gsh = log2i(group_size), ssh = log2i(sel_size);
-  for (int64_t m0 = 0; m0 < M; m0 += 64) {  // 64 rows of x at a time (the packed copy is reused)
-    const int rows = (int)(M - m0 < 64 ? M - m0 : 64);
-    const hipError_t e =
-        rows <= 32 ? launch_rows(fmt, gsh, bits != nullptr, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits,
-                                 sel_stride, tables_bf16, (int)N, (int)K, ssh, y + m0 * ldy, ldy, xpack, cus)
-                   : launch_streaming(fmt, gsh, bits != nullptr, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits,
-                                      sel_stride, tables_bf16, (int)N, (int)K, ssh, y + m0 * ldy, ldy, xpack, cus);
+  for (int64_t m0 = 0; m0 < M; m0 += 32) {  // 32 rows of x at a time (the packed copy is reused)
+    const int rows = (int)(M - m0 < 32 ? M - m0 : 32);
+    const hipError_t e = launch_rows(fmt, gsh, bits != nullptr, stream, xp + m0 * ldx, ldx, rows, codes, scales, bits,
+                                     sel_stride, tables_bf16, (int)N, (int)K, ssh, y + m0 * ldy, ldy, xpack, cus);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

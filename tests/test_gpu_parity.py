@@ -782,13 +782,13 @@ def oracle_args(x, codes, scales, bits, tb, fmt):
     (33, 64, 64, 64, 1, 1),         # one lane quarter of columns
     (200, 1024, 128, 16, 1, 33),    # selection bits from the bit array, three tiles of x rows
     (48, 2048, 32, 32, 0, 64),
-    (130, 4096, 128, 128, 1, 70),   # x in two batches of 64 rows
+    (130, 4096, 128, 128, 1, 70),   # x in three batches: 32, 32 and 6 rows, K split over two blocks
     (20, 512, 16, 16, 1, 17),       # bf16 scales with groups of 16
     (5000, 512, 64, 32, 1, 8),      # many rows: several row tiles per block
     (70, 8192, 16, 16, 0, 16),      # few layer rows: K split over four blocks whose parts are added in y
     (200, 6144, 128, 16, 1, 32),    # two tiles of x rows in registers, K split in three, selection bits
     (1000, 512, 16, 16, 0, 24),     # two tiles of x rows, ragged last block of layer rows
-    (90, 2560, 32, 32, 0, 96),      # 64 rows streamed, the remaining 32 with x in registers
+    (90, 2560, 32, 32, 0, 96),      # three batches of 32 rows of x
     (300, 320, 16, 16, 0, 130),     # more than 64 rows of x: the tiled kernel, ragged tiles in both directions
     (128, 1024, 128, 16, 1, 256),   # tiled, selection bits from the bit array
     (77, 640, 32, 32, 1, 65),       # tiled, one partial tile each way
