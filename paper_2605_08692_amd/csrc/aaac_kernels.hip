@@ -58,30 +58,47 @@ __global__ __launch_bounds__(kStatsBlock) void act_stats_partial_kernel(
   for (int s = 0; s < kStatsStrips; ++s)
 #pragma unroll
     for (int p = 0; p < 8; ++p) acc[s][p] = 0.0;
-  const uint16_t* base = X + col0;
-  for (int64_t t = t0 + wave; t < t1; t += 2 * kStatsWaves) {
-    u32x4 v[2][kStatsStrips];
+  // Two rows are in flight per wavefront, and the one that has just been added is asked for again
+  // (its successor) before the other is added, so loads and additions overlap.  The loads are
+  // unconditional (a load under a branch would make every wait a wait for all loads): a row beyond
+  // the chunk reads the chunk's last row and is not added, a column beyond K reads column 0 of its
+  // strip position and lands in an accumulator that is never stored.
+  const uint16_t* base = X + (col0 < K ? col0 : 0);
+  bool col_ok[kStatsStrips];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int64_t tu = t + (int64_t)u * kStatsWaves;
+  for (int s = 0; s < kStatsStrips; ++s) col_ok[s] = col0 + s * kStripCols < K;
+  auto load_row = [&](u32x4 (&v)[kStatsStrips], int64_t t) {
+    const uint16_t* row = base + (t < t1 ? t : t1 - 1) * ldx;
 #pragma unroll
-      for (int s = 0; s < kStatsStrips; ++s) {
-        v[u][s] = u32x4{0u, 0u, 0u, 0u};
-        if (tu < t1 && col0 + s * kStripCols < K)
-          v[u][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + tu * ldx + s * kStripCols));
+    for (int s = 0; s < kStatsStrips; ++s)
+      v[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (col_ok[s] ? s * kStripCols : 0)));
+  };
+  auto add_row = [&](const u32x4 (&v)[kStatsStrips]) {
+#pragma unroll
+    for (int s = 0; s < kStatsStrips; ++s) {
+      const W8 x = unpack8(make_uint4(v[s].x, v[s].y, v[s].z, v[s].w));
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const double d = (double)x.w[p];
+        acc[s][p] = fma(d, d, acc[s][p]);
       }
     }
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int s = 0; s < kStatsStrips; ++s) {
-        const W8 x = unpack8(make_uint4(v[u][s].x, v[u][s].y, v[u][s].z, v[u][s].w));
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const double d = (double)x.w[p];
-          acc[s][p] = fma(d, d, acc[s][p]);
-        }
-      }
+  };
+  if (t0 + wave < t1) {
+    u32x4 va[kStatsStrips], vb[kStatsStrips];
+    int64_t t = t0 + wave;
+    load_row(va, t);
+    load_row(vb, t + kStatsWaves);
+    for (; t < t1; t += 2 * kStatsWaves) {
+      add_row(va);
+      asm volatile("" ::: "memory");
+      load_row(va, t + 2 * kStatsWaves);
+      asm volatile("" ::: "memory");
+      if (t + kStatsWaves < t1) add_row(vb);
+      asm volatile("" ::: "memory");
+      load_row(vb, t + 3 * kStatsWaves);
+      asm volatile("" ::: "memory");
+    }
   }
   for (int w = 0; w < kStatsWaves; ++w) {
     if (wave == w) {
