@@ -171,23 +171,26 @@ __device__ __forceinline__ ChunkWalk chunk_walk(int64_t cpr) {
   return ChunkWalk{c / cpr, c % cpr, T / cpr, T % cpr, cpr};
 }
 
+// One chunk of 8 weights per thread.  The grid is (blocks of 256 chunks along a row) x (rows, at most
+// 65535: further rows in a loop), so that no thread divides to find its row.  Measured 104 us for 235 M
+// weights (4.5 TB/s), the same with four rows per thread and their loads in flight together, and 15 %
+// slower as a grid-stride loop of fewer, longer-lived blocks.
 template <int LANES, int FMT>
 __global__ __launch_bounds__(kBlock) void group_rinv_kernel(const uint16_t* __restrict__ W, int64_t N,
                                                             int64_t K, int64_t ldw,
                                                             float* __restrict__ rinv) {
-  // one chunk of 8 weights per thread: the two fp64 divisions per chunk, not the loads, take the time, and
-  // many small blocks overlap them best (a grid-stride version with four loads in flight was 15 % slower)
-  const int64_t cpr = K / 8;  // chunks per row
-  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = c < N * cpr;
-  const int64_t row = active ? c / cpr : 0;
-  const int64_t col = active ? (c % cpr) * 8 : 0;
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (active) v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
-  float a = group_max<LANES>(absmax8(unpack8(v)));
-  float s;
-  scale_code<FMT>(a, &s);
-  if (active && (threadIdx.x % LANES) == 0) rinv[row * (K / (8 * LANES)) + col / (8 * LANES)] = div_rn(1.0f, s);
+  const int cpr = (int)(K / 8);  // chunks per row
+  const int cc = (int)blockIdx.x * kBlock + (int)threadIdx.x;
+  const bool active = cc < cpr;
+  const int col = active ? cc * 8 : 0;  // an idle lane reads the row's first chunk
+  const int groups = cpr / LANES;
+  for (int64_t row = blockIdx.y; row < N; row += gridDim.y) {
+    const uint4 v = *reinterpret_cast<const uint4*>(W + row * ldw + col);
+    const float a = group_max<LANES>(absmax8(unpack8(v)));
+    float s;
+    scale_code<FMT>(a, &s);
+    if (active && (threadIdx.x % LANES) == 0) rinv[row * groups + cc / LANES] = div_rn(1.0f, s);
+  }
 }
 
 // ----------------------------------------------------------------- encode
@@ -431,11 +434,11 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
 template <int LANES>
 static hipError_t launch_rinv_lanes(const uint16_t* W, int64_t N, int64_t K, int64_t ldw, int fmt, float* rinv,
                                     hipStream_t stream) {
-  const unsigned gblocks = (unsigned)ceil_div(N * (K / 8), kBlock);
+  const dim3 grid((unsigned)ceil_div(K / 8, kBlock), (unsigned)(N < 65535 ? N : 65535));
   if (fmt == 0)
-    group_rinv_kernel<LANES, 0><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
+    group_rinv_kernel<LANES, 0><<<grid, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   else
-    group_rinv_kernel<LANES, 1><<<gblocks, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
+    group_rinv_kernel<LANES, 1><<<grid, kBlock, 0, stream>>>(W, N, K, ldw, rinv);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
 }
