@@ -73,8 +73,10 @@ def test_random_w4a16_products(seed):
     unit = max(g, 64 if matrix_cores else 32)
     K = unit * int(rng.integers(1, max(2, 4608 // unit)))
     N = int(rng.integers(1, 400))
-    M = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 33, 64, 65, 100, 129, 200, 257, 300])) if matrix_cores \
+    M = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 48, 64, 65, 100, 129, 200, 257, 300])) if matrix_cores \
         else int(rng.integers(1, 20))
+    if matrix_cores and seed % 8 == 7:  # long rows, few of them: K split over several blocks
+        K, N, M = int(rng.choice([6144, 8192, 12288, 16384])), int(rng.integers(1, 130)), int(rng.integers(1, 41))
     while N * K * M > 6.0e7:
         N = max(1, N // 2)
     T.say(f"[sweep {seed}] {'gemm' if matrix_cores else 'gemv'} N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
