@@ -854,6 +854,35 @@ def test_gemm_w4a16_cfg1_full_size_matches_the_product_with_the_dequantised_laye
     assert np.abs(host(y) - full).max() <= 1e-4 * np.abs(full).max()
 
 
+@pytest.mark.parametrize("layer", [0, 1])
+def test_w4a16_products_cfg4_full_size_on_sampled_layer_rows(layer):
+    """The launch configurations that bench.py times on the largest workload: one row (vector ALUs),
+    16 rows (x in registers; down_proj splits K over four blocks) and a ragged 300-row batch (tiles),
+    each checked on every 449th layer row against the oracle."""
+    cfg = inputs.CONFIGS[4]
+    l = cfg["layers"][layer]
+    N, K, g, fmt = l["N"], l["K"], cfg["g"], cfg["fmt"]
+    say(f"[cfg4 products] {l['name']} N={N} K={K}")
+    tb, codes, scales, bits = synthetic_quantised_layer(N, K, g, g, fmt, 9100 + layer)
+    rows = np.arange(0, N, 449)
+    codes_h, scales_h = host(codes)[rows], host(scales).view(np.uint8)[rows]
+    for M in (1, 16, 300):
+        x = (torch.randn((M, K), device=DEV) * 2).to(torch.bfloat16)
+        if M == 1:
+            y = A.aaac_gemv_w4a16(x, codes, scales, bits, tb, g, g, fmt)
+            torch.cuda.synchronize()
+            ref, mag = oracle.gemv_w4a16(inputs.bits(x), codes_h, scales_h, None, u16(tb), g, g, fmt)
+            tol = gemv_tolerance(K, mag)
+        else:
+            y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, g, fmt)
+            torch.cuda.synchronize()
+            ref, mag = oracle.gemm_w4a16(inputs.bits(x), codes_h, scales_h, None, u16(tb), g, g, fmt)
+            tol = (K + 8) * 2.0 ** -24 * mag
+        err = np.abs(host(y)[:, rows].astype(np.float64) - ref)
+        assert (err <= tol + np.spacing(np.abs(ref))).all(), M
+        del x, y
+
+
 def torch_quantile_tables(Wt, g, fmt):
     """The quantile tables from torch's own sort and casts (no library code, no oracle): scales by
     torch's float8 / bf16 conversions, reciprocal through fp64, one fp32 multiply, torch.sort, then
