@@ -387,7 +387,8 @@ void gemm_w4a16_tiled_kernel(
       const int unit = (4 * half + u) ^ (lrow & 7);
       sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
 #pragma unroll
-      for (int xr = 0; xr < kXRows; ++xr) *reinterpret_cast<u32x4*>(&sm.b[lrow + 128 * xr][unit]) = sr.xv[4 * xr + u];  // 128 keeps row & 7
+      for (int xr = 0; xr < kXRows; ++xr)  // rows 128 apart have the same row & 7
+        *reinterpret_cast<u32x4*>(&sm.b[lrow + 128 * xr][unit]) = sr.xv[4 * xr + u];
     }
     __syncthreads();
     // the next stage's loads are in flight during the matrix instructions (the empty statements keep the
@@ -424,7 +425,8 @@ void gemm_w4a16_tiled_kernel(
     }
     __syncthreads();
   }
-  // lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e, x row m_base + wm + 16 j + r
+  // lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e,
+  // x row m_base + wm + 16 j + r
 #pragma unroll
   for (int j = 0; j < kMJ; ++j) {
     const int mm = m_base + wm + 16 * j + r;

@@ -8,9 +8,9 @@
 // counter in LDS, so all wavefronts of a block finish together whatever order
 // the hardware favours them in.  A selection group of S weights (the weights
 // that share a table choice) is held by S/8 adjacent lanes; the scale group
-// (g >= S weights) only decides which reciprocal scale a lane reads.  Up to eight layers are fitted by the same launches: the grid is split
-// among them in proportion to their sizes and a block first looks up the layer
-// it belongs to.
+// (g >= S weights) only decides which reciprocal scale a lane reads.  Up to
+// eight layers are fitted by the same launches: the grid is split among them in
+// proportion to their sizes and a block first looks up the layer it belongs to.
 //
 // Nearest entry: the bucket-table search of aaac_search.h.
 //
