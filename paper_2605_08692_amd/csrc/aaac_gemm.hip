@@ -91,8 +91,7 @@ __global__ void pack_x_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M
 // chunks.  At the end every wavefront writes its 64 x 16 MT partial sums to a slab of its own in
 // LDS (over the pair table, which is no longer needed) and the block adds the 8 slabs while
 // storing y.  x is read once per 64 layer rows and the codes once per 32 rows of x.
-constexpr int kRowsTile = 64;  // layer rows of a block
-constexpr int kRowsTiles = kRowsTile / 16;
+constexpr int kRowsTile = 64;  // layer rows of a block, at most
 constexpr int kSlabPad = 4;  // a slab row is 16 MT + 4 floats: lanes (r, q) of one store fall into 64 banks
 
 template <int MT>
@@ -110,13 +109,14 @@ struct TileRegs {  // what a lane loads per tile of 16 layer rows: 32 code bytes
   uint32_t selbyte;
 };
 
-template <int FMT, int MT, int GS, bool SEL>
+template <int FMT, int MT, int GS, bool SEL, int RT>
 __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_rows_kernel(
     const uint4* __restrict__ xpack, int M, const uint8_t* __restrict__ codes,
     const void* __restrict__ scales, const uint8_t* __restrict__ sel_bits, int64_t sel_stride,
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
     int64_t ldy) {
   __shared__ RowsLds<MT> sm;
+  constexpr int kRowsTile = 16 * RT, kRowsTiles = RT;  // the block's layer rows: 64, or 32 on small layers
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   __syncthreads();
@@ -453,16 +453,22 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
                        const uint16_t* tables_bf16, int N, int K, int ssh, float* y, int64_t ldy, uint4* xpk,
                        int cus) {
   const int chunks = (K + kChunkCols - 1) / kChunkCols;
-  const int row_tiles = (N + kRowsTile - 1) / kRowsTile;
   // With few row tiles the chunk sequence is split over blockIdx.y and the parts are added into y,
   // which the packing kernel clears: two blocks per compute unit if every wavefront still gets two
   // chunks, else one (a block pays about 3 us for its table and the final sum), at least one chunk
-  // per wavefront.
-  int ksplit = (2 * cus + row_tiles / 2) / row_tiles;
-  if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
-    ksplit = (cus + row_tiles / 2) / row_tiles;
-    if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
-    if (ksplit < 1) ksplit = 1;
+  // per wavefront.  If blocks of 64 layer rows still leave a quarter of the compute units without a
+  // block, the blocks take 32 rows (4096 x 4096 at 16 rows: 9.3 us against 10.7; with 224 blocks of
+  // 64 rows on 256 compute units, 14336 x 4096, the smaller blocks were 2 us slower).
+  int rt = 4, row_tiles = 0, ksplit = 1;
+  for (;; rt = 2) {
+    row_tiles = (N + 16 * rt - 1) / (16 * rt);
+    ksplit = (2 * cus + row_tiles / 2) / row_tiles;
+    if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
+      ksplit = (cus + row_tiles / 2) / row_tiles;
+      if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
+      if (ksplit < 1) ksplit = 1;
+    }
+    if (rt == 2 || 4 * row_tiles * ksplit >= 3 * cus) break;
   }
   const int mt = M <= 16 ? 1 : 2;
   const int64_t items = (int64_t)chunks * 8 * mt * 64;
@@ -473,9 +479,15 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const dim3 grid((unsigned)row_tiles, (unsigned)ksplit);
-#define AAAC_ROWS(FMT, MT, GS, SEL)                                                                                  \
-  gemm_w4a16_rows_kernel<FMT, MT, GS, SEL><<<grid, kGemmBlock, 0, stream>>>(xpk, M, codes, scales, bits, sel_stride, \
-                                                                            tables_bf16, N, K, gsh, ssh, y, ldy)
+#define AAAC_ROWS_RT(FMT, MT, GS, SEL, RT)                                                                            \
+  gemm_w4a16_rows_kernel<FMT, MT, GS, SEL, RT><<<grid, kGemmBlock, 0, stream>>>(xpk, M, codes, scales, bits,           \
+                                                                                sel_stride, tables_bf16, N, K, gsh, ssh, \
+                                                                                y, ldy)
+#define AAAC_ROWS(FMT, MT, GS, SEL)                   \
+  do {                                                \
+    if (rt == 4) AAAC_ROWS_RT(FMT, MT, GS, SEL, 4);   \
+    else AAAC_ROWS_RT(FMT, MT, GS, SEL, 2);           \
+  } while (0)
 #define AAAC_ROWS_GS(FMT, MT, SEL)                    \
   do {                                                \
     if (gsh == 4) AAAC_ROWS(FMT, MT, 4, SEL);         \
@@ -495,6 +507,7 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
 #undef AAAC_ROWS_MT
 #undef AAAC_ROWS_GS
 #undef AAAC_ROWS
+#undef AAAC_ROWS_RT
   return hipGetLastError();
 }
 
