@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kGemmBlock) void gemm_w4a16_rows_kernel(
     const uint16_t* __restrict__ tables_bf16, int N, int K, int gshift, int sshift, float* __restrict__ y,
     int64_t ldy) {
   __shared__ RowsLds<MT> sm;
-  constexpr int kRowsTile = 16 * RT, kRowsTiles = RT;  // the block's layer rows: 64, or 32 on small layers
+  constexpr int kRowsTile = 16 * RT, kRowsTiles = RT;  // the block's layer rows: 64, or 32 / 16 on small layers
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 32) sm.T[tid] = __uint_as_float((uint32_t)tables_bf16[tid] << 16);
   __syncthreads();
@@ -457,10 +457,11 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
   // which the packing kernel clears: two blocks per compute unit if every wavefront still gets two
   // chunks, else one (a block pays about 3 us for its table and the final sum), at least one chunk
   // per wavefront.  If blocks of 64 layer rows still leave a quarter of the compute units without a
-  // block, the blocks take 32 rows (4096 x 4096 at 16 rows: 9.3 us against 10.7; with 224 blocks of
-  // 64 rows on 256 compute units, 14336 x 4096, the smaller blocks were 2 us slower).
+  // block, the blocks take 32 rows, then 16 (4096 x 4096 at 16 rows: 9.3 us against 10.7; 1024 x 4096:
+  // 7.2 against 9.4; with 224 blocks of 64 rows on 256 compute units, 14336 x 4096, smaller blocks
+  // were 2 us slower).
   int rt = 4, row_tiles = 0, ksplit = 1;
-  for (;; rt = 2) {
+  for (;; rt /= 2) {
     row_tiles = (N + 16 * rt - 1) / (16 * rt);
     ksplit = (2 * cus + row_tiles / 2) / row_tiles;
     if (ksplit < 1 || chunks / (kGemmWaves * ksplit) < 2) {
@@ -468,7 +469,7 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
       if (ksplit > chunks / kGemmWaves) ksplit = chunks / kGemmWaves;
       if (ksplit < 1) ksplit = 1;
     }
-    if (rt == 2 || 4 * row_tiles * ksplit >= 3 * cus) break;
+    if (rt == 1 || 4 * row_tiles * ksplit >= 3 * cus) break;
   }
   const int mt = M <= 16 ? 1 : 2;
   const int64_t items = (int64_t)chunks * 8 * mt * 64;
@@ -486,7 +487,8 @@ hipError_t launch_rows(int fmt, int gsh, bool sel, hipStream_t stream, const uin
 #define AAAC_ROWS(FMT, MT, GS, SEL)                   \
   do {                                                \
     if (rt == 4) AAAC_ROWS_RT(FMT, MT, GS, SEL, 4);   \
-    else AAAC_ROWS_RT(FMT, MT, GS, SEL, 2);           \
+    else if (rt == 2) AAAC_ROWS_RT(FMT, MT, GS, SEL, 2); \
+    else AAAC_ROWS_RT(FMT, MT, GS, SEL, 1);           \
   } while (0)
 #define AAAC_ROWS_GS(FMT, MT, SEL)                    \
   do {                                                \
