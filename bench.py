@@ -5,17 +5,26 @@ A step is one pass of the whole path over synthetic layers that are already
 resident in HBM: aaac_act_stats (importance from the calibration activations,
 once per distinct input width), aaac_fit / aaac_fit_batch (scales + all Lloyd
 iterations), aaac_encode and aaac_dequant for every layer.  The default workload
-is the Llama-2-7B-shaped q_proj setting (4096x4096 bf16, 65,536 calibration
-tokens, INT4 group 128, 20 iterations); --config selects another of the five
-benchmark settings.
+is the largest of the five benchmark settings, the Llama-3-70B-shaped MLP pair
+(gate 28672x8192 and down 8192x28672 bf16, 131,072 calibration tokens per input
+width, NVFP4 group 16, 30 iterations, one layer fitted after the other);
+--config selects another setting.  The default run also measures the four
+smaller settings, each with its own inputs and a step of the same kind, and
+reports them under `per_config`.
 
 Prints one JSON line.  `value` is weight-iterations per second over the whole
 step (sum of N*K over the layers * passes over the weights / step time).
 `roofline` describes the Lloyd-iteration kernel: its average duration is measured
 with HIP events on the launch stream around every fit call inside the timed
 region (fit time / iterations, so launch gaps and the small scale / init /
-final-table kernels count against it).  `cpu_baseline` is the CPU oracle,
-single-threaded.
+final-table kernels count against it).  `achieved` prices every weight at the
+33 vector-ALU lane operations of the algorithmic model (a count of what the
+method needs, not of what the kernel executes); `counters` holds what the
+hardware counters read for the same kernel (executed lane operations per weight,
+vector-ALU and LDS busy fractions, HBM bytes per launch), taken from
+profiles/counters_lloyd_iter.json when that file was measured on the kernel
+sources as they are now (it carries their hash), else null.  `cpu_baseline` is
+the CPU oracle, single-threaded.
 
 Options beyond the default path (each adds its own object to the line):
 --n-inner / --n-outer run both loops of the learning algorithm (refine_roofline:
@@ -35,9 +44,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # Algorithmic cost of one Lloyd iteration per weight: 2 bytes of bf16 weight plus
-# the group's reciprocal scale (4 bytes per group), and 33 vector-ALU lane
-# operations (unpack 1, normalise 1, two 4-level searches 16, two table look-ups 2,
-# two error chains 8, selection/bin 1, fp64 accumulate 4).
+# the group's stored scale (1 byte per group of an FP8 scale, 2 of a bf16 scale), and 33
+# vector-ALU lane operations (unpack 1, normalise 1, two 4-level searches 16, two table
+# look-ups 2, two error chains 8, selection/bin 1, fp64 accumulate 4).  The kernel itself
+# reads the group's reciprocal scale as an fp32 (4 bytes per group).
 LANE_OPS_PER_WEIGHT = 33.0
 # A refinement pass (choice frozen) searches one table and needs no errors: unpack 1,
 # normalise 1, one search 8, bin 1, fp64 accumulate 4.
@@ -48,39 +58,41 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 
 
 def bytes_per_weight(g):
+    """What the Lloyd kernel reads per weight: the bf16 weight and the group's fp32 reciprocal scale."""
     return 2.0 + 4.0 / g
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=1, help="index into the five benchmark settings")
-    ap.add_argument("--n-inner", type=int, default=1,
-                    help="k-means steps per assignment step (Alg. 1's inner loop); above 1 the fit goes through "
-                         "aaac_fit_nested with --n-outer assignment steps")
-    ap.add_argument("--n-outer", type=int, default=None, help="assignment steps when --n-inner > 1 (default 3)")
-    ap.add_argument("--sel-size", type=int, default=None,
-                    help="weights per table choice when smaller than the scale group (selection bits stored "
-                         "separately); the fit then goes through aaac_fit_nested")
-    ap.add_argument("--quantile-init", action="store_true",
-                    help="start from the quantile tables of Alg. 1 (computed on the GPU inside the fit) instead of "
-                         "the format grid; the fit then goes through aaac_fit_nested")
-    ap.add_argument("--gemv-rows", type=int, default=0,
-                    help="after the timed steps, also time aaac_gemv_w4a16 (the quantised layers applied to this many "
-                         "rows of activations) and report it as gemv_w4a16")
-    ap.add_argument("--gemm-rows", type=int, default=0,
-                    help="the same for aaac_gemm_w4a16 (matrix cores, weights rounded to bf16), reported as gemm_w4a16")
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def algorithmic_bytes_per_weight(g, fmt_is_nvfp4):
+    """What the method needs per weight: the bf16 weight and the group's stored scale."""
+    return 2.0 + (1.0 if fmt_is_nvfp4 else 2.0) / g
 
+
+def kernel_source_hash():
+    """Hash of the sources of the Lloyd-iteration kernel (counter summaries carry it)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("aaac_lloyd.hip", "aaac_search.h", "aaac_device.h", "aaac_internal.h"):
+        with open(os.path.join(ROOT, "paper_2605_08692_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_counters(workload):
+    """Hardware-counter figures of the Lloyd kernel on `workload`, or None when there are none for the
+    kernel as it is now."""
+    path = os.path.join(ROOT, "profiles", "counters_lloyd_iter.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        data = json.load(f)
+    if data.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return data.get("workloads", {}).get(workload)
+
+
+def measure(args, cfg_id, steps_arg, warmup_arg, cpu_baseline, extras):
+    """One setting: inputs, buffers, warm-up, timed steps; returns the JSON object of that setting.
+    extras: also run what the options ask for beyond the timed steps (products, copy calibration)."""
     import numpy as np
     import torch
 
@@ -90,10 +102,10 @@ def main():
     A.library()  # no fallback: fails here if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    cfg = inputs.CONFIGS[args.config]
-    big = args.config >= 3
-    steps = args.steps if args.steps is not None else (3 if big else 20)
-    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+    cfg = inputs.CONFIGS[cfg_id]
+    default_steps = {0: 50, 1: 20, 2: 20, 3: 10, 4: 25}[cfg_id]  # cfg4: 25 x 14.5 ms, a timed region of about a third of a second
+    steps = steps_arg if steps_arg is not None else default_steps
+    warmup = warmup_arg if warmup_arg is not None else (2 if cfg_id >= 3 else 3)
     g, fmt, iters = cfg["g"], cfg["fmt"], cfg["iters"]
     grid = inputs.format_grid(fmt)
     fit_grid = None if args.quantile_init else grid   # None: quantile tables, taken on the GPU inside the fit
@@ -274,19 +286,17 @@ def main():
         return {"rows_of_x": Mx, "bound": bound, "peak_GBs": HBM_PEAK_GBS, "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
                 "layers": per_layer}
 
-    gemv = time_product(args.gemv_rows, False) if args.gemv_rows > 0 else None
-    gemm = time_product(args.gemm_rows, True) if args.gemm_rows > 0 else None
+    gemv = time_product(args.gemv_rows, False) if extras and args.gemv_rows > 0 else None
+    gemm = time_product(args.gemm_rows, True) if extras and args.gemm_rows > 0 else None
 
-    if args.copy_calibration:
+    if extras and args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
         b.copy_(a)
         torch.cuda.synchronize()
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_lloyd_iter_cfg{args.config}.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    counters = measured_counters(cfg["name"]) if not nested else None
+    traffic = counters.get("hbm_bytes_per_launch") if counters else None
 
     x_bytes = sum(X.numel() * 2 for X in Xs.values())
     achieved = LANE_OPS_PER_WEIGHT * weights_per_s_iter / 1e12
@@ -315,8 +325,14 @@ def main():
         "roofline": {"bound": "alu", "kernel": "lloyd_iter_kernel", "achieved": achieved,
                      "peak": ALU_PEAK_TLANEOPS, "unit": "Tlane-op/s", "frac": achieved / ALU_PEAK_TLANEOPS,
                      "traffic": traffic,
-                     "hbm_achieved_GBs": bytes_per_weight(g) * weights_per_s_iter / 1e9,
-                     "hbm_frac": bytes_per_weight(g) * weights_per_s_iter / 1e9 / HBM_PEAK_GBS},
+                     "model_lane_ops_per_weight": LANE_OPS_PER_WEIGHT,
+                     "counters": counters,
+                     "algorithmic_bytes_per_weight": algorithmic_bytes_per_weight(g, fmt == A.NVFP4),
+                     "bytes_read_per_weight": bytes_per_weight(g),
+                     "hbm_achieved_GBs": algorithmic_bytes_per_weight(g, fmt == A.NVFP4) * weights_per_s_iter / 1e9,
+                     "hbm_frac": algorithmic_bytes_per_weight(g, fmt == A.NVFP4) * weights_per_s_iter / 1e9
+                     / HBM_PEAK_GBS},
+        "weights": n_w,
     }
 
     if refine is not None:
@@ -329,7 +345,7 @@ def main():
         out["quantile_init"] = quant
         out["config"]["init"] = "quantile"
 
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         # bounded sample: the oracle's fit of (a row slice of) the first layer, all iterations
         L = layers[0]
@@ -347,6 +363,56 @@ def main():
                                "kind": "oracle",
                                "sample": f'oracle fit of {rows} of the {L["N"]} rows of {L["name"]} '
                                          f'({rows}x{L["K"]}), all {passes} passes, {dt:.1f} s on one host core'}
+    return out
+
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=4, help="index into the five benchmark settings")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the measurement of the smaller settings that the default run adds as per_config")
+    ap.add_argument("--n-inner", type=int, default=1,
+                    help="k-means steps per assignment step (Alg. 1's inner loop); above 1 the fit goes through "
+                         "aaac_fit_nested with --n-outer assignment steps")
+    ap.add_argument("--n-outer", type=int, default=None, help="assignment steps when --n-inner > 1 (default 3)")
+    ap.add_argument("--sel-size", type=int, default=None,
+                    help="weights per table choice when smaller than the scale group (selection bits stored "
+                         "separately); the fit then goes through aaac_fit_nested")
+    ap.add_argument("--quantile-init", action="store_true",
+                    help="start from the quantile tables of Alg. 1 (computed on the GPU inside the fit) instead of "
+                         "the format grid; the fit then goes through aaac_fit_nested")
+    ap.add_argument("--gemv-rows", type=int, default=0,
+                    help="after the timed steps, also time aaac_gemv_w4a16 (the quantised layers applied to this many "
+                         "rows of activations) and report it as gemv_w4a16")
+    ap.add_argument("--gemm-rows", type=int, default=0,
+                    help="the same for aaac_gemm_w4a16 (matrix cores, weights rounded to bf16), reported as gemm_w4a16")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    out = measure(args, args.config, args.steps, args.warmup, cpu_baseline=not args.no_cpu_baseline, extras=True)
+    plain = (args.n_inner == 1 and args.sel_size is None and not args.quantile_init and args.config == 4)
+    if plain and not args.no_per_config:
+        # the smaller settings in the same run: same kind of step, their own inputs, fewer details
+        per = {}
+        for c in range(4):
+            r = measure(args, c, None, None, cpu_baseline=False, extras=False)
+            per[r["config"]["workload"]] = {
+                "weights": r["weights"], "steps": r["steps"], "ms_per_step": r["ms_per_step"],
+                "stage_ms": r["stage_ms"], "act_stats_GBs": r["act_stats_GBs"],
+                "lloyd_iteration_us": r["lloyd_iteration_us"], "lloyd_weights_per_s": r["lloyd_weights_per_s"],
+                "frac": r["roofline"]["frac"], "counters": r["roofline"]["counters"],
+                "note": ("launch-bound: 131,072 weights are two per resident lane" if c == 0 else None)}
+        out["per_config"] = per
     print(json.dumps(out))
 
 

@@ -16,9 +16,12 @@
  *   - Matrices are row-major with a leading dimension in elements; weight groups
  *     of `group_size` run along the input dimension K of W [N x K].
  *   - Return value: AAAC_OK or a negative aaac_status_t.  Arguments are validated
- *     on the host before any HIP call, so argument errors are reported without a
- *     GPU; a failed launch gives AAAC_ERR_HIP.  Not checked: that W, X and the
- *     importances are finite and the importances non-negative.
+ *     on the host before any HIP call, and the workspace queries make none, so
+ *     argument errors and workspace sizes are reported without a GPU; a failed
+ *     launch gives AAAC_ERR_HIP.  Not checked: that W, X and the importances are
+ *     finite and the importances non-negative.
+ *   - The launch paths ask the runtime for the current device's compute-unit
+ *     count at every call; nothing is cached between calls or across devices.
  *   - Matrix pointers may be NULL when N == 0 (nothing is read or written).
  *   - Shapes: K % group_size == 0, group_size in {16, 32, 64, 128}, leading
  *     dimensions >= K and multiples of 8, device matrices and the importance
@@ -34,8 +37,8 @@
 extern "C" {
 #endif
 
-/* Scale format of a group (paper section 3.1, "a scale s is computed from the
- * group's weight statistics"; constants are those of the two benchmark settings):
+/* Scale format of a group (paper section 3.1, base quantiser; Alg. 1 step 1; the
+ * constants are those of the two benchmark settings):
  *   NVFP4: stored scale = OCP FP8 E4M3 (nearest-even, saturating) of absmax/6, 1 byte
  *   INT4 : stored scale = bf16 (nearest-even) of absmax/7, 2 bytes
  * A scale that would be 0 (or, for bf16, subnormal) is replaced by the smallest

@@ -123,7 +123,7 @@ int aaac_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float*
 
 size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt) {
   if (N < 0 || K < 0 || !valid_group(group_size) || !valid_fmt(fmt) || K % group_size != 0) return 0;
-  return aaac::make_fit_plan(N, K, K, group_size, group_size).bytes;
+  return aaac::fit_layout(N, K, group_size, group_size).bytes;
 }
 
 size_t aaac_quantile_init_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt) {
@@ -137,7 +137,7 @@ int aaac_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int gro
   if (rc) return rc;
   if (N == 0 || K == 0) return AAAC_ERR_SHAPE;
   if (!valid_fmt(fmt)) return AAAC_ERR_ARG;
-  const aaac::FitPlan p = aaac::make_fit_plan(N, K, ldw, group_size, group_size);
+  const aaac::FitLayout p = aaac::fit_layout(N, K, group_size, group_size);
   rc = check_ws(ws, ws_bytes, p.bytes);
   if (rc) return rc;
   char* base = static_cast<char*>(ws);
@@ -177,7 +177,7 @@ size_t aaac_fit_nested_workspace(const aaac_layer_t* layers, int n_layers, int g
   for (int i = 0; i < n_layers; ++i) {
     const int64_t N = layers[i].N, K = layers[i].K;
     if (N < 0 || K < 0 || K % group_size != 0) return 0;
-    total += align256(aaac::make_fit_plan(N, K, K, group_size, sel_size).bytes);
+    total += align256(aaac::fit_layout(N, K, group_size, sel_size).bytes);
   }
   return total;
 }
@@ -217,7 +217,7 @@ int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, in
     for (int i = first; i < n_layers && n < aaac::kMaxFusedLayers; ++i, ++n) {
       const aaac_layer_t& l = layers[i];
       tasks[n] = {l.W, l.N, l.K, l.ldw, l.importance, l.tables_f32, l.tables_bf16, l.objective_trace, base};
-      base += align256(aaac::make_fit_plan(l.N, l.K, l.ldw, group_size, sel_size).bytes);
+      base += align256(aaac::fit_layout(l.N, l.K, group_size, sel_size).bytes);
     }
     if (aaac::launch_fit_group(tasks, n, group_size, sel_size, fmt, init_grid ? &grid : nullptr, n_outer, n_inner,
                                stream) != hipSuccess)

@@ -534,14 +534,7 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
     }
     return hipSuccess;
   }
-  static int cus = 0;  // compute units of the device, asked once (256 on MI355X)
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    cus = hipGetDevice(&dev) == hipSuccess &&
-                  hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0
-              ? n
-              : 256;
-  }
+  const int cus = device_compute_units();
   const uint8_t* bits = sel_size < group_size ? sel_bits : nullptr;
   const uint16_t* xp = static_cast<const uint16_t*>(x);
   // Large batches take the tiled kernel, which pays the dequantisation once per 128 or 256 rows of x

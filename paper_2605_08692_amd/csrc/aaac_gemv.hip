@@ -300,14 +300,7 @@ hipError_t launch_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
     }
     return hipSuccess;
   }
-  static int cus = 0;  // compute units of the device, asked once (256 on MI355X)
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    cus = hipGetDevice(&dev) == hipSuccess &&
-                  hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0
-              ? n
-              : 256;
-  }
+  const int cus = device_compute_units();
   // two blocks fit a compute unit; rows per block bounded by the row-sum buffer
   int64_t rpb = (N + 2 * cus - 1) / (2 * cus);
   if (rpb < 8) rpb = 8;

@@ -59,11 +59,20 @@ struct FitPlan {
   int strip_groups;      // ceil(strips / strips_per_block)
   int rows_per_block;
   int blocks;            // strip_groups * ceil(N / rows_per_block)
-  // workspace layout (byte offsets)
+};
+// cus: compute units this layer may fill (at least 1).
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cus);
+
+// Byte offsets of the parts of a layer's fit workspace; depends on the shape only (no device query).
+struct FitLayout {
   size_t off_state, off_rinv, off_sigma, off_quant, bytes;
 };
-// cu_budget: compute units this layer may fill (0 = all of the device's).
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cu_budget = 0);
+FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size);
+
+// Compute units of the current device, asked from the runtime at every call (256 on MI355X, also the
+// value returned when no device can be asked).  Launch paths only: argument checks and workspace
+// queries never call it.
+int device_compute_units();
 
 struct StatsPlan {
   int strips;             // column groups of 4096
@@ -83,7 +92,7 @@ struct FitTask {
   float* tables_f32;
   uint16_t* tables_bf16;
   double* objective_trace;
-  void* ws;  // this layer's workspace (make_fit_plan(...).bytes)
+  void* ws;  // this layer's workspace (fit_layout(...).bytes)
 };
 constexpr int kMaxFusedLayers = 8;  // layers whose iterations share one launch
 // grid == nullptr: the initial tables are the quantiles of each layer's normalised weights.

@@ -471,7 +471,7 @@ struct EncodeCall {
 
 template <int LANES>
 static hipError_t launch_encode_lanes(const EncodeCall& c, hipStream_t stream) {
-  const FitPlan p = make_fit_plan(c.N, c.K, c.ldw, c.group_size, 8 * LANES);
+  const FitPlan p = make_fit_plan(c.N, c.K, c.ldw, c.group_size, 8 * LANES, device_compute_units());
 #define AAAC_ENCODE(FMT, SAME)                                                                              \
   encode_kernel<LANES, FMT, SAME><<<p.blocks, kSearchBlock, 0, stream>>>(                                    \
       c.W, (int)c.N, (int)c.K, c.ldw, c.importance, c.tables_bf16, c.codes, c.scales, c.sel_bits, c.sel_stride, \

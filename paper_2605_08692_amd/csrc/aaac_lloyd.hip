@@ -365,21 +365,6 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchAr
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Compute units of the current device (256 on MI355X); the default is used when
-// no device is visible, e.g. for a workspace query on a host without a GPU.
-int compute_units() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cached = n;
-    else
-      cached = 256;
-  }
-  return cached;
-}
-
 // Index in the objective trace that the sums of pass p carry (-1: none).
 int trace_index(int p, int n_inner) { return p >= 0 && p % n_inner == 0 ? p / n_inner : -1; }
 
@@ -400,7 +385,27 @@ hipError_t launch_passes(const BatchArgs& batch, int blocks, int n_outer, int n_
 
 }  // namespace
 
-FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cu_budget) {
+int device_compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+    return n;
+  return 256;
+}
+
+FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size) {
+  auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  FitLayout p;
+  p.off_state = 0;
+  p.off_rinv = align(sizeof(FitState));
+  const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
+  p.off_sigma = p.off_rinv + align(groups * sizeof(float));
+  p.off_quant = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
+  p.bytes = p.off_quant + align(sizeof(QuantState));
+  return p;
+}
+
+FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel_size, int cus) {
   FitPlan p;
   p.N = N; p.K = K; p.ldw = ldw; p.group_size = group_size; p.sel_size = sel_size;
   p.strips = (int)ceil_div(K > 0 ? K : 1, kStripCols);
@@ -410,7 +415,7 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel
   // possible without exceeding the compute units (all blocks resident at once, no
   // second round), few wavefronts bound to strips past the last one, and at least
   // one row per wavefront.
-  const int cus = cu_budget > 0 ? cu_budget : compute_units();
+  if (cus < 1) cus = 1;
   double best = -1.0;
   for (int spb = 1; spb <= kLloydWaves; spb *= 2) {
     const int64_t groups = ceil_div(p.strips, spb);
@@ -432,13 +437,6 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel
       p.blocks = (int)blocks;
     }
   }
-  auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p.off_state = 0;
-  p.off_rinv = align(sizeof(FitState));
-  const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
-  p.off_sigma = p.off_rinv + align(groups * sizeof(float));
-  p.off_quant = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
-  p.bytes = p.off_quant + align(sizeof(QuantState));
   return p;
 }
 
@@ -453,22 +451,23 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
   for (int g = group_size; g > 1; g >>= 1) ++work.gshift;
   double total = 0.0;
   for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
-  const int cus = compute_units();
+  const int cus = device_compute_units();
   int blocks = 0;
   for (int i = 0; i < n; ++i) {
     const FitTask& t = tasks[i];
     const double share = total > 0.0 ? (double)t.N * (double)t.K / total : 0.0;
     int budget = (int)(share * cus);
     if (budget < 1) budget = 1;
-    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, n == 1 ? 0 : budget);
+    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, n == 1 ? cus : budget);
+    const FitLayout lay = fit_layout(t.N, t.K, group_size, sel_size);
     char* base = static_cast<char*>(t.ws);
     LayerArgs a = {};
     a.W = static_cast<const uint16_t*>(t.W);
-    a.rinv = reinterpret_cast<const float*>(base + p.off_rinv);
+    a.rinv = reinterpret_cast<const float*>(base + lay.off_rinv);
     a.importance = t.importance;
-    a.state = reinterpret_cast<FitState*>(base + p.off_state);
-    a.sigma = n_inner > 1 ? reinterpret_cast<uint8_t*>(base + p.off_sigma) : nullptr;
-    QuantState* qs = reinterpret_cast<QuantState*>(base + p.off_quant);
+    a.state = reinterpret_cast<FitState*>(base + lay.off_state);
+    a.sigma = n_inner > 1 ? reinterpret_cast<uint8_t*>(base + lay.off_sigma) : nullptr;
+    QuantState* qs = reinterpret_cast<QuantState*>(base + lay.off_quant);
     a.grid_dev = grid ? nullptr : qs->grid;
     a.objective_trace = t.objective_trace;
     a.tables_f32 = t.tables_f32;

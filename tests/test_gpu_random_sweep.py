@@ -21,21 +21,21 @@ def rand_weight(rng, N, K, seed):
     W = inputs.make_weight(N, K, "gauss_outlier" if kind % 2 == 0 else "student5", seed, DEV)
     if kind == 2:    # all-zero rows and leading groups
         W[int(rng.integers(0, N))] = 0
-        W[:, : 16 * int(rng.integers(1, max(2, K // 32)))] *= (torch.rand(N, 1, device=DEV) < 0.7).to(torch.bfloat16)
+        W[:, : 16 * int(rng.integers(1, max(2, K // 32)))] *= (torch.rand(N, 1, device=DEV, generator=T.seeded(10 * seed + 1)) < 0.7).to(torch.bfloat16)
     elif kind == 3:  # rows of very different magnitude
-        W = (W.float() * torch.exp(torch.randn(N, 1, device=DEV) * 4)).to(torch.bfloat16)
+        W = (W.float() * torch.exp(torch.randn(N, 1, device=DEV, generator=T.seeded(10 * seed + 2)) * 4)).to(torch.bfloat16)
     elif kind == 4:  # few distinct values: ties in every search
         W = (torch.round(W.float() * 200) / 200).to(torch.bfloat16)
     return W
 
 
-def rand_importance(rng, K):
-    I = torch.rand(K, device=DEV) * float(10 ** rng.uniform(-3, 3)) + 1e-6
+def rand_importance(rng, K, seed):
+    I = torch.rand(K, device=DEV, generator=T.seeded(10 * seed + 3)) * float(10 ** rng.uniform(-3, 3)) + 1e-6
     k = int(rng.integers(0, 3))
     if k == 1:
-        I[torch.rand(K, device=DEV) < 0.2] = 0
+        I[torch.rand(K, device=DEV, generator=T.seeded(10 * seed + 4)) < 0.2] = 0
     elif k == 2:
-        I[torch.rand(K, device=DEV) < 0.02] *= 1e4
+        I[torch.rand(K, device=DEV, generator=T.seeded(10 * seed + 5)) < 0.02] *= 1e4
     return I
 
 
@@ -53,7 +53,7 @@ def test_random_fit_encode_dequant(seed):
     pad = int(rng.integers(0, 3))
     quantile = bool(rng.integers(0, 3) == 0)
     T.say(f"[sweep {seed}] N={N} K={K} g={g} S={S} fmt={fmt} outer={n_outer} inner={n_inner} pad={pad} quantile={quantile}")
-    W, I = rand_weight(rng, N, K, 5000 + seed), rand_importance(rng, K)
+    W, I = rand_weight(rng, N, K, 5000 + seed), rand_importance(rng, K, 5000 + seed)
     grid = None
     if quantile:
         grid = oracle.quantile_init(inputs.bits(W), g, fmt)
@@ -81,7 +81,7 @@ def test_random_w4a16_products(seed):
         N = max(1, N // 2)
     T.say(f"[sweep {seed}] {'gemm' if matrix_cores else 'gemv'} N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
     tb, codes, scales, bits = T.synthetic_quantised_layer(N, K, g, S, fmt, 7000 + seed)
-    x = (torch.randn((M, K), device=DEV) * 2).to(torch.bfloat16)
+    x = (torch.randn((M, K), device=DEV, generator=T.seeded(70000 + seed)) * 2).to(torch.bfloat16)
     if matrix_cores:
         y = A.aaac_gemm_w4a16(x, codes, scales, bits, tb, g, S, fmt)
         torch.cuda.synchronize()
