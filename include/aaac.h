@@ -8,7 +8,8 @@
  *   - "dev" pointers are HIP device pointers on the current device; "HOST"
  *     pointers are ordinary host memory, read before the call returns.
  *   - The caller owns every buffer.  The library allocates nothing, keeps no state
- *     between calls and never synchronises: all work is enqueued on `hip_stream`
+ *     between calls (aaac_act_stats_static excepted, see there) and never
+ *     synchronises: all work is enqueued on `hip_stream`
  *     (a hipStream_t passed as void*, NULL = the default stream); outputs are
  *     valid once the caller has synchronised that stream.  Two calls may run
  *     concurrently if they use different workspaces and outputs.
@@ -65,6 +66,23 @@ const char* aaac_status_string(int status);
 size_t aaac_act_stats_workspace(int64_t tokens, int64_t K);
 int aaac_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---- aaac_act_stats for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, the same result bit for bit, with the partial sums kept in an 8 MiB array
+ * that is part of the library's device code, so no workspace is passed and neither
+ * this call nor anything it calls allocates or frees memory.
+ *   - Limit: K <= 1,048,576 columns (what 8 MiB of partial sums hold); a larger K is
+ *     AAAC_ERR_WORKSPACE.  Other arguments and errors as aaac_act_stats.
+ *   - Each GPU the library runs on holds its own copy of the array until the process
+ *     ends.  The first call on a device looks up that copy's address (one runtime
+ *     query, kept per device); make that first call outside graph capture.
+ *   - All calls on one GPU share the array: calls that overlap on one GPU (different
+ *     streams, or threads) race and give wrong sums; calls on one stream are ordered.
+ *     Nothing has to be cleared between calls: every partial sum a call reads, it has
+ *     written before. */
+int aaac_act_stats_static(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                          void* hip_stream);
 
 /* ---- Codebook learning (paper Alg. 1 from "compute scales" to the end of the
  * outer loop, with n_inner = 1 and caller-supplied initial tables; Eq.

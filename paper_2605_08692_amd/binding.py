@@ -50,6 +50,8 @@ def library():
         L.aaac_act_stats_workspace.argtypes = [_I64, _I64]
         L.aaac_act_stats.restype = _INT
         L.aaac_act_stats.argtypes = [_P, _I64, _I64, _I64, _P, _P, _SZ, _P]
+        L.aaac_act_stats_static.restype = _INT
+        L.aaac_act_stats_static.argtypes = [_P, _I64, _I64, _I64, _P, _P]
         L.aaac_fit_workspace.restype = _SZ
         L.aaac_fit_workspace.argtypes = [_I64, _I64, _INT, _INT]
         L.aaac_fit.restype = _INT
@@ -133,6 +135,17 @@ def aaac_act_stats(X, importance=None, ws=None, stream=None):
     ldx = X.stride(0) if tokens > 1 else max(X.stride(0), K)
     _check(library().aaac_act_stats(_dp(X), tokens, K, ldx, _dp(importance), _dp(ws), ws.numel(),
                                     _stream(stream)), "aaac_act_stats")
+    return importance
+
+
+def aaac_act_stats_static(X, importance, stream=None):
+    """aaac_act_stats with the partial sums in the library's own device array: no workspace, and
+    `importance` must be given (nothing is allocated here either)."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.stride(1) == 1
+    tokens, K = X.shape
+    ldx = X.stride(0) if tokens > 1 else max(X.stride(0), K)
+    _check(library().aaac_act_stats_static(_dp(X), tokens, K, ldx, _dp(importance), _stream(stream)),
+           "aaac_act_stats_static")
     return importance
 
 

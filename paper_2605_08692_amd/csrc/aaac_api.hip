@@ -121,6 +121,18 @@ int aaac_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float*
                                          static_cast<hipStream_t>(hip_stream)));
 }
 
+int aaac_act_stats_static(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                          void* hip_stream) {
+  if (importance == nullptr || (X == nullptr && tokens > 0)) return AAAC_ERR_NULL;
+  if (tokens < 0 || K <= 0 || K % 8 != 0 || ldx < K || ldx % 8 != 0) return AAAC_ERR_SHAPE;
+  if (tokens > (int64_t)1 << 40 || K > (int64_t)1 << 31) return AAAC_ERR_SHAPE;
+  if (!aligned(X, 16)) return AAAC_ERR_SHAPE;
+  aaac::StatsPlan plan = aaac::make_stats_plan(tokens, K);
+  if (plan.bytes > aaac::kStaticScratchBytes) return AAAC_ERR_WORKSPACE;  // K beyond what the array holds
+  return from_hip(aaac::launch_act_stats_static(X, tokens, K, ldx, importance, plan,
+                                                static_cast<hipStream_t>(hip_stream)));
+}
+
 size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt) {
   if (N < 0 || K < 0 || !valid_group(group_size) || !valid_fmt(fmt) || K % group_size != 0) return 0;
   return aaac::fit_layout(N, K, group_size, group_size).bytes;

@@ -84,6 +84,11 @@ StatsPlan make_stats_plan(int64_t tokens, int64_t K);
 
 hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
                             void* ws, const StatsPlan& plan, hipStream_t stream);
+// The same with the partial sums in the library's own device array (no workspace from the caller);
+// plan.bytes must not exceed kStaticScratchBytes.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+hipError_t launch_act_stats_static(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                                   const StatsPlan& plan, hipStream_t stream);
 // One layer of a fit as the launcher sees it (host side).
 struct FitTask {
   const void* W;

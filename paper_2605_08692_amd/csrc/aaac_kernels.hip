@@ -7,6 +7,8 @@
 // IEEE operations (the file is compiled with -ffp-contract=off).  This file holds
 // the importance, scale, encode and dequant kernels; the Lloyd iteration is in
 // aaac_lloyd.hip, the nearest-entry search shared with it in aaac_search.h.
+#include <atomic>
+
 #include "aaac_device.h"
 #include "aaac_internal.h"
 #include "aaac_search.h"
@@ -429,6 +431,45 @@ hipError_t launch_act_stats(const void* X, int64_t tokens, int64_t K, int64_t ld
                                                                                  K, Kpad, importance);
   AAAC_LAUNCH_CHECK();
   return hipSuccess;
+}
+
+// ---- partial sums of the importance without a caller's workspace
+//
+// The array lives in the library's device code; every GPU that loads the library holds its own
+// copy at its own address.  In host code the array's name is only a handle for the runtime: the
+// address a kernel can use comes from hipGetSymbolAddress, asked once per device with that device
+// current and kept in scratch_ptr[]; kernels get that pointer as an argument, exactly as they get
+// the caller's workspace in launch_act_stats.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> scratch_ptr[kMaxDevices];
+
+static hipError_t static_scratch(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    scratch_ptr[dev].store(p, std::memory_order_release);  // two first calls at once store the same address
+  }
+  *out = p;
+  return hipSuccess;
+}
+
+hipError_t launch_act_stats_static(const void* X, int64_t tokens, int64_t K, int64_t ldx, float* importance,
+                                   const StatsPlan& plan, hipStream_t stream) {
+  if (plan.bytes > kStaticScratchBytes) return hipErrorInvalidValue;
+  void* ws = nullptr;
+  if (tokens > 0) {
+    hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return e;
+  }
+  return launch_act_stats(X, tokens, K, ldx, importance, ws, plan, stream);
 }
 
 template <int LANES>

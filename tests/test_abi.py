@@ -90,6 +90,12 @@ def test_other_entry_points_validate():
     assert L.aaac_act_stats(FAKE, 4, 64, 32, FAKE, FAKE, 1 << 20, None) == E_SHAPE
     assert L.aaac_act_stats(FAKE, -4, 64, 64, FAKE, FAKE, 1 << 20, None) == E_SHAPE
     assert L.aaac_act_stats(FAKE, 4, 64, 64, FAKE, FAKE, 8, None) == E_WS
+    # the variant without a workspace: same checks, and a K beyond what its own array holds
+    assert L.aaac_act_stats_static(None, 4, 64, 64, FAKE, None) == E_NULL
+    assert L.aaac_act_stats_static(FAKE, 4, 64, 64, None, None) == E_NULL
+    assert L.aaac_act_stats_static(FAKE, 4, 60, 64, FAKE, None) == E_SHAPE
+    assert L.aaac_act_stats_static(FAKE, 4, 64, 32, FAKE, None) == E_SHAPE
+    assert L.aaac_act_stats_static(FAKE, 4, (1 << 20) + 4096, (1 << 20) + 4096, FAKE, None) == E_WS
     assert L.aaac_encode(FAKE, 8, 64, 64, 16, 0, FAKE, FAKE, None, FAKE, None) == E_NULL
     assert L.aaac_encode(FAKE, 8, 64, 64, 48, 0, FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
     assert L.aaac_encode(FAKE, 8, 64, 64, 16, 7, FAKE, FAKE, FAKE, FAKE, None) == E_ARG
