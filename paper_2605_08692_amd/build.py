@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libaaac.so")
-SOURCES = ["aaac_api.hip", "aaac_kernels.hip", "aaac_lloyd.hip", "aaac_quantile.hip", "aaac_gemv.hip", "aaac_gemm.hip"]
+SOURCES = ["aaac_api.hip", "aaac_kernels.hip", "aaac_lloyd.hip", "aaac_small.hip", "aaac_quantile.hip", "aaac_gemv.hip", "aaac_gemm.hip"]
 
 # -ffp-contract=off: every fp32 operation that decides a code or a selection bit
 # must stay a single IEEE operation.  Packed fp32 instructions are switched off.

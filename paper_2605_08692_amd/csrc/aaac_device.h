@@ -38,6 +38,23 @@ __device__ __forceinline__ float e4m3_value(uint32_t c) {  // c in 0..0x7E
 // values rounds to fp32 the same way the exact quotient does).
 __device__ __forceinline__ float div_rn(float a, float b) { return (float)((double)a / (double)b); }
 
+// Scale of a group from its absmax (FMT 0: FP8 E4M3 of absmax / 6; FMT 1: bf16 of absmax / 7; a
+// scale that would be zero, or a subnormal bf16, becomes the smallest positive value); returns the
+// unsigned stored code and the scale's value in *s.
+template <int FMT>
+__device__ __forceinline__ uint32_t scale_code(float absmax, float* s) {
+  if (FMT == 0) {
+    uint32_t c = e4m3_rne_sat(div_rn(absmax, 6.0f));
+    c = c == 0u ? 1u : c;
+    *s = e4m3_value(c);
+    return c;
+  }
+  uint32_t c = bf16_rne(div_rn(absmax, 7.0f));
+  c = c < 0x80u ? 0x80u : c;
+  *s = __uint_as_float(c << 16);
+  return c;
+}
+
 // ---- DPP lane exchanges -------------------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp(float v) {

@@ -65,7 +65,7 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel
 
 // Byte offsets of the parts of a layer's fit workspace; depends on the shape only (no device query).
 struct FitLayout {
-  size_t off_state, off_rinv, off_sigma, off_quant, bytes;
+  size_t off_state, off_rinv, off_sigma, off_quant, off_small, bytes;
 };
 FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size);
 
@@ -118,6 +118,22 @@ hipError_t launch_dequant(const uint8_t* codes, const void* scales, const uint8_
                           int64_t sel_stride, const uint16_t* tables_bf16, int64_t N, int64_t K,
                           int group_size, int sel_size, int fmt, void* W_hat, int64_t ldo,
                           hipStream_t stream);
+
+// ---- a small layer fitted by one launch (aaac_small.hip)
+constexpr int kSmallMaxBlocks = 32;  // blocks that exchange their partial sums
+constexpr int kSmallRows = 8;        // rows of a strip that one wavefront keeps in registers
+constexpr int kSmallWords = 130;     // 64-bit words per block and pass: 65 sums, two tagged halves each
+constexpr size_t kSmallStateBytes = (size_t)2 * kSmallMaxBlocks * kSmallWords * sizeof(unsigned long long);
+struct SmallPlan {
+  int blocks;  // 0: the layer is too large for this path
+  int strips, waves_per_strip, rows_per_wave;
+};
+SmallPlan make_small_plan(int64_t N, int64_t K);
+// grid: the caller's initial tables, or null when grid_dev already holds them (quantile initialisation,
+// enqueued before).  grid_dev: 32 floats of device memory; words: kSmallStateBytes of device memory.
+hipError_t launch_fit_small(const FitTask& t, const SmallPlan& plan, int group_size, int sel_size, int fmt,
+                            const Grid32* grid, float* grid_dev, unsigned long long* words, int n_outer,
+                            int n_inner, hipStream_t stream);
 
 constexpr int kGemvMaxRows = 128;  // output rows one block of the W4A16 product accumulates
 // y[M x ldy] fp32 = x[M x ldx] bf16 times the quantised layer (codes, scales, tables), K % 32 == 0.

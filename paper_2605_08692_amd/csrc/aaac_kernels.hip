@@ -19,21 +19,6 @@ namespace {
 
 constexpr int kBlock = 256;
 
-// Scale of a group from its absmax; returns the unsigned stored code.
-template <int FMT>
-__device__ __forceinline__ uint32_t scale_code(float absmax, float* s) {
-  if (FMT == 0) {
-    uint32_t c = e4m3_rne_sat(div_rn(absmax, 6.0f));
-    c = c == 0u ? 1u : c;
-    *s = e4m3_value(c);
-    return c;
-  }
-  uint32_t c = bf16_rne(div_rn(absmax, 7.0f));
-  c = c < 0x80u ? 0x80u : c;
-  *s = __uint_as_float(c << 16);
-  return c;
-}
-
 // ------------------------------------------------------------ importance
 
 // Partial column sums of squares over one chunk of tokens.  A wavefront reads

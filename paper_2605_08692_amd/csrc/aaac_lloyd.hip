@@ -29,6 +29,9 @@
 // rotate (read t-1, add to t, clear t+1), and the tables are double-buffered, so
 // a slow block never races with a fast one.  The order of the cross-block adds
 // is not fixed: sums can differ between runs in the last bits of an fp64.
+#include <cstdlib>
+#include <cstring>
+
 #include "aaac_device.h"
 #include "aaac_internal.h"
 #include "aaac_search.h"
@@ -45,7 +48,6 @@ constexpr int kLloydWaves = kSearchWaves;
 struct alignas(16) LloydLds {
   SearchTables st;
   double hist[2][32][kSlots];             // [0] = sum I*x, [1] = sum I
-  float cand[32];
   double sums[72];
   double red[kLloydWaves];
   double copies[kAccCopies][kAccStride];  // the accumulator copies, staged by 16 wavefronts
@@ -90,18 +92,9 @@ __device__ __forceinline__ void device_add(double* p, double v) {
 // and the bucket of every midpoint.  Lanes of one wavefront run in lockstep and
 // LDS accesses of a wavefront complete in order, so its stores are visible to
 // its own later loads; wave_barrier() only keeps the compiler from reordering.
-// One step of the rank count: the entry K lanes away in the row of 16 (value and index, both rotated
-// the same way) against this lane's; equal values rank by index.
-template <int K>
-__device__ __forceinline__ void rank_step(float v, int i, int& rank) {
-  constexpr int kRor = 0x120 + K;  // row_ror:K
-  const float u = dpp<kRor>(v);
-  const int j = __builtin_amdgcn_update_dpp(0, i, kRor, 0xF, 0xF, false);
-  rank += (u < v || (u == v && j < i)) ? 1 : 0;
-}
-
 __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) {
   const int lane = threadIdx.x & 63;
+  float entry = 0.0f;
   if (lane < 32) {
     float t = old_entry;  // lane b holds entry b of the previous tables
     if (have_sums) {  // the copies are added in a fixed order
@@ -115,32 +108,9 @@ __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) 
       if (lane == 0) sm.sums[64] = obj;
       if (den > 0.0) t = (float)(num / den);
     }
-    sm.cand[lane] = t;
+    entry = t;
   }
-  __builtin_amdgcn_wave_barrier();
-  {  // stable rank sort inside each table: a table is one row of 16 lanes, the other 15 entries come
-     // by lane rotation together with their indices (16 dependent LDS reads took 0.7 us here)
-    const int base = lane & 16, i = lane & 15;
-    const float v = lane < 32 ? sm.cand[lane] : 0.0f;
-    int rank = 0;
-    rank_step<1>(v, i, rank);
-    rank_step<2>(v, i, rank);
-    rank_step<3>(v, i, rank);
-    rank_step<4>(v, i, rank);
-    rank_step<5>(v, i, rank);
-    rank_step<6>(v, i, rank);
-    rank_step<7>(v, i, rank);
-    rank_step<8>(v, i, rank);
-    rank_step<9>(v, i, rank);
-    rank_step<10>(v, i, rank);
-    rank_step<11>(v, i, rank);
-    rank_step<12>(v, i, rank);
-    rank_step<13>(v, i, rank);
-    rank_step<14>(v, i, rank);
-    rank_step<15>(v, i, rank);
-    if (lane < 32) sm.st.newtab[base + rank] = v;
-  }
-  wave_make_rows(sm.st);
+  wave_sort_tables(sm.st, entry);
 }
 
 // pass: index of this pass (selects the accumulator and table buffers);
@@ -365,6 +335,9 @@ __global__ __launch_bounds__(kLloydBlock) void final_tables_kernel(const BatchAr
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Layers up to this many (row, strip) pairs take the one-launch path by default.
+constexpr int64_t kSmallAutoUnits = 512;
+
 // Index in the objective trace that the sums of pass p carry (-1: none).
 int trace_index(int p, int n_inner) { return p >= 0 && p % n_inner == 0 ? p / n_inner : -1; }
 
@@ -401,7 +374,8 @@ FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size) {
   const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
   p.off_sigma = p.off_rinv + align(groups * sizeof(float));
   p.off_quant = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
-  p.bytes = p.off_quant + align(sizeof(QuantState));
+  p.off_small = p.off_quant + align(sizeof(QuantState));
+  p.bytes = p.off_small + align(kSmallStateBytes);
   return p;
 }
 
@@ -444,6 +418,30 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
                             const Grid32* grid, int n_outer, int n_inner, hipStream_t stream) {
   const int iterations = n_outer;
   if (n <= 0) return hipSuccess;
+  // A single small layer: all passes in one launch (AAAC_FIT_PATH=launches keeps it on the
+  // launch-per-pass path, =persistent sends every layer that fits; default: up to kSmallAutoUnits rows of strips).
+  if (n == 1 && tasks[0].N > 0 && tasks[0].K > 0) {
+    const FitTask& t = tasks[0];
+    const SmallPlan sp = make_small_plan(t.N, t.K);
+    const char* path = std::getenv("AAAC_FIT_PATH");
+    const bool never = path != nullptr && std::strcmp(path, "launches") == 0;
+    const bool always = path != nullptr && std::strcmp(path, "persistent") == 0;
+    const int64_t units = t.N * (int64_t)sp.strips;
+    if (sp.blocks > 0 && !never && (always || units <= kSmallAutoUnits)) {
+      const FitLayout lay = fit_layout(t.N, t.K, group_size, sel_size);
+      char* base = static_cast<char*>(t.ws);
+      QuantState* qs = reinterpret_cast<QuantState*>(base + lay.off_quant);
+      if (!grid) {
+        float* rinv = reinterpret_cast<float*>(base + lay.off_rinv);
+        hipError_t e = launch_group_rinv(t.W, t.N, t.K, t.ldw, group_size, fmt, rinv, stream);
+        if (e != hipSuccess) return e;
+        e = launch_quantile_init(t.W, t.N, t.K, t.ldw, group_size, rinv, qs, qs->grid, stream);
+        if (e != hipSuccess) return e;
+      }
+      return launch_fit_small(t, sp, group_size, sel_size, fmt, grid, qs->grid,
+                              reinterpret_cast<unsigned long long*>(base + lay.off_small), n_outer, n_inner, stream);
+    }
+  }
   // every layer gets its state initialised and its outputs written; only layers
   // that hold weights take part in the iterations
   BatchArgs all = {}, work = {};

@@ -47,11 +47,16 @@ struct alignas(16) SearchTables {
   uint32_t entry[2][kBuckets];  // unreplicated bucket entries while building
 };
 
-struct alignas(16) SearchLut {
+// REPL: copies of every bucket entry (a power of two up to 32).  32 copies make the data-dependent
+// look-ups of a wavefront conflict-free; kernels that see only a few rows per launch take fewer
+// copies, because building the table then costs more than the conflicts.
+template <int REPL>
+struct alignas(16) SearchLutT {
   // per table: byte offset of the candidate row from row[0][0] (16 * row, plus
   // sizeof(row[0]) for table 1), replicated
-  uint32_t lut[2][kBuckets * kReplicas];
+  uint32_t lut[2][kBuckets * REPL];
 };
+using SearchLut = SearchLutT<kReplicas>;
 
 // Monotone map from a normalised weight to the byte offset of its bucket's
 // replica block (bucket * 128): integer part of fma(x, inv, off), read from the
@@ -60,6 +65,13 @@ __device__ __forceinline__ uint32_t bucket_row(float x, float inv, float off) {
   float t = __builtin_fmaf(x, inv, off);
   t = __builtin_amdgcn_fmed3f(t, 8388608.0f, 8388608.0f + 32767.0f);
   return __float_as_uint(t) & 0x7F80u;
+}
+// The same as the byte offset of the bucket's first copy in a table of REPL copies (bucket * 4 * REPL).
+template <int REPL>
+__device__ __forceinline__ uint32_t bucket_offset(float x, float inv, float off) {
+  static_assert(REPL == 1 || REPL == 2 || REPL == 4 || REPL == 8 || REPL == 16 || REPL == 32, "copies per bucket");
+  const uint32_t b = bucket_row(x, inv, off);
+  return REPL == 32 ? b : b / (32u / REPL);
 }
 
 __device__ __forceinline__ float tree8(const float (&u)[8]) {
@@ -74,8 +86,9 @@ struct Lane8 {
   float p0, p1;           // the lane's partial error sums
 };
 
+template <int REPL>
 __device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&Iv)[8], const SearchTables& st,
-                                            const SearchLut& sl, float inv, float off, uint32_t rep4, Lane8& a) {
+                                            const SearchLutT<REPL>& sl, float inv, float off, uint32_t rep4, Lane8& a) {
   float u0[8], u1[8];
   const char* lut = reinterpret_cast<const char*>(sl.lut);
   const char* rows = reinterpret_cast<const char*>(st.row[0]);
@@ -83,7 +96,7 @@ __device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&
   for (int p = 0; p < 8; ++p) {
     const float wn = x.w[p] * r;
     a.wn[p] = wn;
-    const char* e = lut + (bucket_row(wn, inv, off) | rep4);
+    const char* e = lut + (bucket_offset<REPL>(wn, inv, off) | rep4);
     const uint32_t a0 = *reinterpret_cast<const uint32_t*>(e);
     const uint32_t a1 = *reinterpret_cast<const uint32_t*>(e + sizeof(sl.lut[0]));
     // each row is one 16-byte DS read; all four fields are used, so it is not narrowed
@@ -96,6 +109,52 @@ __device__ __forceinline__ void assign_fast(const W8& x, float r, const float (&
     const float d1 = wn - (c1 ? s1.z : s1.y);
     a.k0[p] = __float_as_uint(s0.w);
     a.k1[p] = __float_as_uint(s1.w);
+    a.m0[p] = __builtin_amdgcn_ballot_w64(c0);
+    a.m1[p] = __builtin_amdgcn_ballot_w64(c1);
+    const float q0 = d0 * d0;
+    const float q1 = d1 * d1;
+    u0[p] = Iv[p] * q0;
+    u1[p] = Iv[p] * q1;
+  }
+  a.p0 = tree8(u0);
+  a.p1 = tree8(u1);
+}
+
+// The same as assign_fast with the look-ups of the 8 weights issued together (all bucket reads, then all
+// row reads, then the arithmetic): more registers, but a wavefront that has the SIMD almost to itself
+// does not wait for one LDS read after the other.
+template <int REPL>
+__device__ __forceinline__ void assign_fast_batched(const W8& x, float r, const float (&Iv)[8], const SearchTables& st,
+                                                    const SearchLutT<REPL>& sl, float inv, float off, uint32_t rep4,
+                                                    Lane8& a) {
+  float u0[8], u1[8];
+  const char* lut = reinterpret_cast<const char*>(sl.lut);
+  const char* rows = reinterpret_cast<const char*>(st.row[0]);
+  uint32_t a0[8], a1[8];
+  f32x4 s0[8], s1[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    a.wn[p] = x.w[p] * r;
+    const char* e = lut + (bucket_offset<REPL>(a.wn[p], inv, off) | rep4);
+    a0[p] = *reinterpret_cast<const uint32_t*>(e);
+    a1[p] = *reinterpret_cast<const uint32_t*>(e + sizeof(sl.lut[0]));
+  }
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    s0[p] = *reinterpret_cast<const f32x4*>(rows + a0[p]);
+    s1[p] = *reinterpret_cast<const f32x4*>(rows + a1[p]);
+  }
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const float wn = a.wn[p];
+    const bool c0 = wn > s0[p].x;
+    const bool c1 = wn > s1[p].x;
+    const float d0 = wn - (c0 ? s0[p].z : s0[p].y);
+    const float d1 = wn - (c1 ? s1[p].z : s1[p].y);
+    a.k0[p] = __float_as_uint(s0[p].w);
+    a.k1[p] = __float_as_uint(s1[p].w);
     a.m0[p] = __builtin_amdgcn_ballot_w64(c0);
     a.m1[p] = __builtin_amdgcn_ballot_w64(c1);
     const float q0 = d0 * d0;
@@ -143,7 +202,8 @@ struct Lane8One {
   float check;
 };
 
-__device__ __forceinline__ void assign_one_fast(const W8& x, float r, const SearchTables& st, const SearchLut& sl,
+template <int REPL>
+__device__ __forceinline__ void assign_one_fast(const W8& x, float r, const SearchTables& st, const SearchLutT<REPL>& sl,
                                                 float inv, float off, uint32_t rep4_table, Lane8One& a) {
   const char* lut = reinterpret_cast<const char*>(sl.lut);
   const char* rows = reinterpret_cast<const char*>(st.row[0]);
@@ -152,7 +212,7 @@ __device__ __forceinline__ void assign_one_fast(const W8& x, float r, const Sear
   for (int p = 0; p < 8; ++p) {
     const float wn = x.w[p] * r;
     a.wn[p] = wn;
-    const uint32_t e = *reinterpret_cast<const uint32_t*>(lut + (bucket_row(wn, inv, off) | rep4_table));
+    const uint32_t e = *reinterpret_cast<const uint32_t*>(lut + (bucket_offset<REPL>(wn, inv, off) | rep4_table));
     const f32x4 s = *reinterpret_cast<const f32x4*>(rows + e);
     a.k[p] = __float_as_uint(s.w);
     a.m[p] = __builtin_amdgcn_ballot_w64(wn > s.x);
@@ -207,9 +267,11 @@ __device__ __forceinline__ void wave_make_rows(SearchTables& st) {
   }
 }
 
-// Bucket table from the midpoint buckets, replicated; all kSearchBlock threads
-// of the block call it after wave_make_rows() and a barrier.  Ends with a barrier.
-__device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLut& sl) {
+// Bucket table from the midpoint buckets, replicated; all BLOCK threads of the block
+// (at least 2 * kBuckets) call it after wave_make_rows() and a barrier.  Ends with a barrier.
+template <int REPL, int BLOCK = kSearchBlock>
+__device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLutT<REPL>& sl) {
+  static_assert(BLOCK >= 2 * kBuckets && BLOCK % REPL == 0, "one thread per bucket and table");
   const int tid = threadIdx.x;
   if (tid < 2 * kBuckets) {  // one thread per bucket and table
     const int r = tid / kBuckets, b = tid % kBuckets;
@@ -221,15 +283,59 @@ __device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLut& 
       inside += bj == b ? 1 : 0;
     }
     const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
-    st.entry[r][b] = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
+    const uint32_t e = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
+    if constexpr (REPL == 4) {  // the four copies are one 16-byte store: no staging, one barrier less
+      *reinterpret_cast<uint4*>(&sl.lut[r][b * REPL]) = make_uint4(e, e, e, e);
+    } else {
+      st.entry[r][b] = e;
+    }
   }
   __syncthreads();
-  // replicate: thread -> (replica = tid % 32, buckets tid/32 + 32*k)
-  for (int b = tid / kReplicas; b < kBuckets; b += kSearchBlock / kReplicas) {
-    sl.lut[0][b * kReplicas + (tid % kReplicas)] = st.entry[0][b];
-    sl.lut[1][b * kReplicas + (tid % kReplicas)] = st.entry[1][b];
+  if constexpr (REPL == 4) return;
+  // replicate: thread -> (copy = tid % REPL, buckets tid / REPL + (BLOCK / REPL) * k)
+  for (int b = tid / REPL; b < kBuckets; b += BLOCK / REPL) {
+    sl.lut[0][b * REPL + (tid % REPL)] = st.entry[0][b];
+    sl.lut[1][b * REPL + (tid % REPL)] = st.entry[1][b];
   }
   __syncthreads();
+}
+
+// One step of the rank count of wave_sort_tables: the entry K lanes away in the row of 16 (value and
+// index, both rotated the same way) against this lane's; equal values rank by index.
+template <int K>
+__device__ __forceinline__ void rank_step(float v, int i, int& rank) {
+  constexpr int kRor = 0x120 + K;  // row_ror:K
+  const float u = dpp<kRor>(v);
+  const int j = __builtin_amdgcn_update_dpp(0, i, kRor, 0xF, 0xF, false);
+  rank += (u < v || (u == v && j < i)) ? 1 : 0;
+}
+
+// Called by ONE wavefront (all 64 lanes): lane b < 32 passes entry b of the two tables (T0 in lanes
+// 0..15, T1 in 16..31).  Sorts each table (stable rank sort: a table is one row of 16 lanes, the other
+// 15 entries come by lane rotation together with their indices), leaves them in st.newtab and
+// builds the search rows (wave_make_rows).
+__device__ __forceinline__ void wave_sort_tables(SearchTables& st, float entry) {
+  const int lane = threadIdx.x & 63;
+  const int base = lane & 16, i = lane & 15;
+  const float v = lane < 32 ? entry : 0.0f;
+  int rank = 0;
+  rank_step<1>(v, i, rank);
+  rank_step<2>(v, i, rank);
+  rank_step<3>(v, i, rank);
+  rank_step<4>(v, i, rank);
+  rank_step<5>(v, i, rank);
+  rank_step<6>(v, i, rank);
+  rank_step<7>(v, i, rank);
+  rank_step<8>(v, i, rank);
+  rank_step<9>(v, i, rank);
+  rank_step<10>(v, i, rank);
+  rank_step<11>(v, i, rank);
+  rank_step<12>(v, i, rank);
+  rank_step<13>(v, i, rank);
+  rank_step<14>(v, i, rank);
+  rank_step<15>(v, i, rank);
+  if (lane < 32) st.newtab[base + rank] = v;
+  wave_make_rows(st);
 }
 
 }  // namespace aaac

@@ -5,6 +5,7 @@ Bars: scale codes, 4-bit codes, selection bits, bf16 tables and dequantised
 weights bit-exact; fp32 tables within 1e-5 relative (+1e-6 of the table's range
 near zero); importance within 1e-6 relative; objective within 1e-9 relative.
 """
+import contextlib
 import json
 import os
 import time
@@ -29,6 +30,25 @@ def say(*a):
 def seeded(seed):
     """A generator on the test device with a fixed seed: every random draw of these tests names one."""
     return torch.Generator(device=DEV).manual_seed(int(seed))
+
+
+@contextlib.contextmanager
+def fit_path(name):
+    """Route the fits inside the block through one of the library's two paths: "launches" (one launch
+    per pass over the weights) or "persistent" (all passes of a small layer in one launch); layers
+    the persistent path does not take go through launches either way."""
+    old = os.environ.get("AAAC_FIT_PATH")
+    os.environ["AAAC_FIT_PATH"] = name
+    try:
+        yield
+    finally:
+        if old is None:
+            del os.environ["AAAC_FIT_PATH"]
+        else:
+            os.environ["AAAC_FIT_PATH"] = old
+
+
+FIT_PATHS = ("launches", "persistent")
 
 
 def tables_close(gpu, ref):
@@ -56,26 +76,29 @@ def check_layer(Wt, I_host, g, fmt, grid, iters, label, check_dequant=True):
     ref = oracle.fit(Wb, g, fmt, I_host, grid, iters, trace=True)
     rc, rs = oracle.encode(Wb, g, fmt, I_host, ref["tables_bf16"])
     say(f"[parity] {label}: oracle {time.time() - t0:.1f}s")
-    tf, tb, obj = A.aaac_fit(Wt, g, fmt, It, grid, iters)
+    for path in FIT_PATHS:  # both ways through the library (the same one for layers too large for "persistent")
+        with fit_path(path):
+            tf, tb, obj = A.aaac_fit(Wt, g, fmt, It, grid, iters)
+            torch.cuda.synchronize()
+            tfh, tbh = host(tf), u16(tb)
+            if not (tbh == ref["tables_bf16"]).all() or not tables_close(tfh, ref["tables_f32"]):
+                # locate the first iteration whose tables differ, to tell a 1-ulp flip from a bug
+                for t in range(1, iters + 1):
+                    tft, _, _ = A.aaac_fit(Wt, g, fmt, It, grid, t)
+                    torch.cuda.synchronize()
+                    d = host(tft) != ref["tables_trace"][t - 1]
+                    if d.any():
+                        say(f"[parity] {label} ({path}): first table difference at iteration {t}: entries "
+                            f"{np.nonzero(d)[0]}", host(tft)[d], ref["tables_trace"][t - 1][d])
+                        break
+        assert tables_close(tfh, ref["tables_f32"]), (path, tfh, ref["tables_f32"])
+        assert (tbh == ref["tables_bf16"]).all(), path
+        if iters:
+            o = host(obj)[:iters]
+            assert np.allclose(o, ref["objective"], rtol=1e-9, atol=0), (path, o, ref["objective"])
     codes, scales = A.aaac_encode(Wt, g, fmt, It, tb)
     What = A.aaac_dequant(codes, scales, tb, g, fmt)
     torch.cuda.synchronize()
-    tfh, tbh = host(tf), u16(tb)
-    if not (tbh == ref["tables_bf16"]).all() or not tables_close(tfh, ref["tables_f32"]):
-        # locate the first iteration whose tables differ, to tell a 1-ulp flip from a bug
-        for t in range(1, iters + 1):
-            tft, _, _ = A.aaac_fit(Wt, g, fmt, It, grid, t)
-            torch.cuda.synchronize()
-            d = host(tft) != ref["tables_trace"][t - 1]
-            if d.any():
-                say(f"[parity] {label}: first table difference at iteration {t}: entries {np.nonzero(d)[0]}",
-                    host(tft)[d], ref["tables_trace"][t - 1][d])
-                break
-    assert tables_close(tfh, ref["tables_f32"]), (tfh, ref["tables_f32"])
-    assert (tbh == ref["tables_bf16"]).all()
-    if iters:
-        o = host(obj)[:iters]
-        assert np.allclose(o, ref["objective"], rtol=1e-9, atol=0), (o, ref["objective"])
     sc = host(scales).view(rs.dtype)
     assert (sc == rs).all(), f"{(sc != rs).sum()} scale/selection mismatches"
     ch = host(codes)
@@ -399,11 +422,22 @@ def test_batch_of_more_layers_than_one_launch_group_and_an_empty_layer():
 
 
 def nested_on_gpu(Ws, Is, g, fmt, grid, n_outer, n_inner, S=None):
-    layers, outs = A.make_layers(Ws, Is, n_outer)
-    ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt, sel_size=S), dtype=torch.uint8, device=DEV)
-    A.aaac_fit_nested(layers, g, fmt, grid, n_outer, n_inner, ws, sel_size=S)
-    torch.cuda.synchronize()
-    return outs
+    """aaac_fit_nested through both of the library's paths; the two must agree (bf16 tables bit for
+    bit), and the callers compare the returned one with the oracle."""
+    results = []
+    for path in FIT_PATHS:
+        layers, outs = A.make_layers(Ws, Is, n_outer)
+        ws = torch.empty(A.aaac_fit_nested_workspace(layers, g, fmt, sel_size=S), dtype=torch.uint8, device=DEV)
+        with fit_path(path):
+            A.aaac_fit_nested(layers, g, fmt, grid, n_outer, n_inner, ws, sel_size=S)
+            torch.cuda.synchronize()
+        results.append(outs)
+    for (tf0, tb0, ob0), (tf1, tb1, ob1) in zip(*results):
+        assert (u16(tb0) == u16(tb1)).all(), "the two fit paths give different bf16 tables"
+        assert np.allclose(host(tf0), host(tf1), rtol=1e-6, atol=0)
+        if n_outer:
+            assert np.allclose(host(ob0)[:n_outer], host(ob1)[:n_outer], rtol=1e-9, atol=0)
+    return results[1]
 
 
 @pytest.mark.parametrize("N,K,g,fmt,n_outer,n_inner", [
