@@ -94,24 +94,30 @@ __device__ __forceinline__ void device_add(double* p, double v) {
 // its own later loads; wave_barrier() only keeps the compiler from reordering.
 __device__ void wave_make_tables(LloydLds& sm, bool have_sums, float old_entry) {
   const int lane = threadIdx.x & 63;
-  float entry = 0.0f;
-  if (lane < 32) {
-    float t = old_entry;  // lane b holds entry b of the previous tables
-    if (have_sums) {  // the copies are added in a fixed order
-      double num = 0.0, den = 0.0, obj = 0.0;
+  float entry = old_entry;  // lane b < 32 holds entry b of the previous tables
+  if (have_sums) {
+    // Lane l adds element l of the copies: lanes 0..31 the numerators, lanes 32..63 the denominators of
+    // the same entries, 16 loads in flight and a fixed tree of additions; lane 0 also adds the objective.
+    double v[kAccCopies];
 #pragma unroll
-      for (int c = 0; c < kAccCopies; ++c) {
-        num += sm.copies[c][lane];
-        den += sm.copies[c][32 + lane];
-        if (lane == 0) obj += sm.copies[c][64];
-      }
-      if (lane == 0) sm.sums[64] = obj;
-      if (den > 0.0) t = (float)(num / den);
+    for (int c = 0; c < kAccCopies; ++c) v[c] = sm.copies[c][lane];
+    static_assert(kAccCopies == 16, "tree of 16");
+#pragma unroll
+    for (int w = 1; w < kAccCopies; w *= 2)
+#pragma unroll
+      for (int c = 0; c < kAccCopies; c += 2 * w) v[c] += v[c + w];
+    const double den = __shfl_down(v[0], 32);
+    if (lane == 0) {
+      double obj = 0.0;
+#pragma unroll
+      for (int c = 0; c < kAccCopies; ++c) obj += sm.copies[c][64];
+      sm.sums[64] = obj;
     }
-    entry = t;
+    if (lane < 32 && den > 0.0) entry = (float)(v[0] / den);
   }
   wave_sort_tables(sm.st, entry);
 }
+
 
 // pass: index of this pass (selects the accumulator and table buffers);
 // prev_trace: where the objective found in the previous pass's sums goes (-1: nowhere);

@@ -292,10 +292,20 @@ __device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLutT<
   }
   __syncthreads();
   if constexpr (REPL == 4) return;
-  // replicate: thread -> (copy = tid % REPL, buckets tid / REPL + (BLOCK / REPL) * k)
-  for (int b = tid / REPL; b < kBuckets; b += BLOCK / REPL) {
-    sl.lut[0][b * REPL + (tid % REPL)] = st.entry[0][b];
-    sl.lut[1][b * REPL + (tid % REPL)] = st.entry[1][b];
+  // replicate with 16-byte stores: unit u of 4 copies -> table u / (kBuckets * REPL / 4), bucket
+  // (u / (REPL / 4)) % kBuckets; consecutive threads write consecutive units
+  if constexpr (REPL >= 4) {
+    constexpr int kUnitsPerBucket = REPL / 4, kUnits = 2 * kBuckets * kUnitsPerBucket;
+    uint4* dst = reinterpret_cast<uint4*>(&sl.lut[0][0]);
+    for (int u = tid; u < kUnits; u += BLOCK) {
+      const uint32_t e = (&st.entry[0][0])[u / kUnitsPerBucket];
+      dst[u] = make_uint4(e, e, e, e);
+    }
+  } else {
+    for (int b = tid / REPL; b < kBuckets; b += BLOCK / REPL) {
+      sl.lut[0][b * REPL + (tid % REPL)] = st.entry[0][b];
+      sl.lut[1][b * REPL + (tid % REPL)] = st.entry[1][b];
+    }
   }
   __syncthreads();
 }

@@ -95,14 +95,8 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
   uint32_t sigbits = 0;  // bit j: the choice of this lane's selection group in row j
   if (tid == 0) sm.failed = 0;
 
-#ifdef AAAC_SMALL_TIMING
-#define AAAC_STAMP(i) if (tid == 0 && b == 0 && pass < passes) a.objective_trace[64 + pass * 8 + (i)] = (double)wall_clock64();
-#else
-#define AAAC_STAMP(i)
-#endif
   const int passes = a.n_outer * a.n_inner;
   for (int pass = 0; pass <= passes; ++pass) {
-    AAAC_STAMP(0)
     // the tables of this pass (after the last pass: the final tables), by wavefront 0
     if (wave == 0) {
       float entry = 0.0f;
@@ -120,9 +114,7 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
     if (pass == passes) break;
     for (int i = tid; i < 2 * 32 * kSlots; i += kSmallBlock) (&sm.hist[0][0][0])[i] = 0.0;
     __syncthreads();
-    AAAC_STAMP(1)
     build_bucket_table<kSmallRepl, kSmallBlock>(sm.st, sm.sl);
-    AAAC_STAMP(2)
     const float inv = sm.st.lutpar[0], off = sm.st.lutpar[1];
     const bool assign = pass % a.n_inner == 0;
     double obj = 0.0;
@@ -171,7 +163,6 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
     for (int o = 32; o > 0; o >>= 1) obj += __shfl_down(obj, o);
     if (lane == 0) sm.red[wave] = obj;
     __syncthreads();
-    AAAC_STAMP(3)
     // Thread (bin = tid / 8, part = tid % 8): the block's sum of `bin` from the kSlots copies (4 neighbouring
     // slots per thread, then across the 8 threads), published by the thread with part 0 as two tagged
     // words; the thread with part 1 of bin 0 publishes the block's share of the objective.
@@ -200,7 +191,6 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
                            __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    AAAC_STAMP(4)
     // Collect: the same thread waits for the two words of `bin` from blocks part, part + 8, part + 16,
     // part + 24 (its own block's included) and, if tid < B, for the objective words of block tid.
     double total = 0.0;
@@ -240,7 +230,6 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
           break;
         }
       }
-      AAAC_STAMP(5)
       // totals in a fixed order: blocks part, part + 8, ... in this thread, then across the 8 threads
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -252,7 +241,6 @@ __global__ __launch_bounds__(kSmallBlock) void small_fit_kernel(const SmallArgs 
       if (tid < B) sm.objs[tid] = __longlong_as_double((long long)(((unsigned long long)half[9] << 32) | half[8]));
     }
     __syncthreads();
-    AAAC_STAMP(6)
     if (sm.failed) break;
     if (tid == 64 && b == 0 && assign && a.objective_trace) {  // off the path to the next tables
       double s = 0.0;
