@@ -456,13 +456,50 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
   double total = 0.0;
   for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
   const int cus = device_compute_units();
+  // Compute units per layer.  All layers' blocks run side by side in one launch, one block per compute
+  // unit, so a pass takes as long as the layer with the most weights per block: start from each layer's
+  // share rounded down, then hand the compute units that are left, one step at a time, to the layer whose
+  // blocks are the largest (a layer's block count moves in steps: strips x row chunks).
+  FitPlan plans[kMaxFusedLayers];
+  {
+    int budget[kMaxFusedLayers];
+    bool stuck[kMaxFusedLayers];
+    int used = 0;
+    for (int i = 0; i < n; ++i) {
+      const FitTask& t = tasks[i];
+      const double share = total > 0.0 ? (double)t.N * (double)t.K / total : 0.0;
+      budget[i] = n == 1 ? cus : (int)(share * cus);
+      if (budget[i] < 1) budget[i] = 1;
+      plans[i] = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, budget[i]);
+      stuck[i] = !(t.N > 0 && t.K > 0);
+      used += stuck[i] ? 0 : plans[i].blocks;
+    }
+    for (int round = 0; round < 64 && used < cus; ++round) {
+      int j = -1;
+      double worst = 0.0;
+      for (int i = 0; i < n; ++i) {
+        const double load = (double)tasks[i].N * (double)tasks[i].K / (double)plans[i].blocks;
+        if (!stuck[i] && load > worst) { worst = load; j = i; }
+      }
+      if (j < 0) break;
+      bool grown = false;
+      for (int extra = 1; extra <= 16 && !grown; ++extra) {
+        const FitTask& t = tasks[j];
+        const FitPlan q = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, budget[j] + extra);
+        if (q.blocks > plans[j].blocks && used - plans[j].blocks + q.blocks <= cus) {
+          used += q.blocks - plans[j].blocks;
+          budget[j] += extra;
+          plans[j] = q;
+          grown = true;
+        }
+      }
+      if (!grown) stuck[j] = true;
+    }
+  }
   int blocks = 0;
   for (int i = 0; i < n; ++i) {
     const FitTask& t = tasks[i];
-    const double share = total > 0.0 ? (double)t.N * (double)t.K / total : 0.0;
-    int budget = (int)(share * cus);
-    if (budget < 1) budget = 1;
-    const FitPlan p = make_fit_plan(t.N, t.K, t.ldw, group_size, sel_size, n == 1 ? cus : budget);
+    const FitPlan& p = plans[i];
     const FitLayout lay = fit_layout(t.N, t.K, group_size, sel_size);
     char* base = static_cast<char*>(t.ws);
     LayerArgs a = {};
