@@ -239,10 +239,11 @@ int aaac_gemv_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_t* codes,
  *   y[m, n] = sum_k x[m, k] * w^[n, k]
  * so the result is the fp32-accumulated product of x with the dequantised layer, without
  * that layer ever being written.  Small batches go 32 rows of x at a time, which stay in
- * registers while the codes are read once (layers with few rows split K over blocks and
- * add the parts into y with atomics whose order is not fixed: results may differ between
- * runs in the last bits); large batches use 128 x 128 / 128 x 256 tiles whose weights
- * are dequantised once per tile.
+ * registers while the codes are read once; large batches use 128 x 128 / 128 x 256 tiles
+ * whose weights are dequantised once per tile.  Where the layer's rows (small batches) or
+ * the tiles (large batches) are fewer than the compute units, K is split over blocks that
+ * add their parts into y with atomics whose order is not fixed: results may then differ
+ * between runs in the last bits.
  * Arguments and errors as aaac_gemv_w4a16, except K % 64 == 0, scales 8-byte aligned, and
  *   ws       dev scratch of aaac_gemm_w4a16_workspace(M, K) bytes, 256-byte aligned (x
  *            is first copied into the matrix instruction's operand order); too small or

@@ -361,10 +361,15 @@ void gemm_w4a16_tiled_kernel(
 #pragma unroll
       for (int u = 0; u < 4; ++u) sr.xv[4 * xr + u] = *reinterpret_cast<const u32x4*>(xrow[xr] + k0 + 8 * u);
   };
+  // blockIdx.z: which part of K this block sums (stages of 64 columns; with more than one part the
+  // parts are added into y, which the host has cleared)
+  const int stages = K / kTileK;
+  const int k_begin = (int)((int64_t)stages * blockIdx.z / gridDim.z) * kTileK;
+  const int k_end = (int)((int64_t)stages * (blockIdx.z + 1) / gridDim.z) * kTileK;
   StageRegs sr;
-  fetch(sr, 0);
+  fetch(sr, k_begin);
   __builtin_assume(K >= kTileK);  // checked by the host
-  for (int k_stage = 0; k_stage < K; k_stage += kTileK) {
+  for (int k_stage = k_begin; k_stage < k_end; k_stage += kTileK) {
     const int k0 = k_stage + 32 * half;
     // dequantise the 32 weights: two 16-column blocks with their scale and selection
     const uint32_t cw[4] = {sr.cw4.x, sr.cw4.y, sr.cw4.z, sr.cw4.w};
@@ -425,20 +430,39 @@ void gemm_w4a16_tiled_kernel(
     }
     __syncthreads();
   }
-  // lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e,
-  // x row m_base + wm + 16 j + r
+  // Lane (r, q) holds D[4q + e][r] of each 16 x 16 tile: layer rows n_base + wn + 16 i + 4q + e, x row
+  // m_base + wm + 16 j + r.  Rows of y run along the layer rows, so a wavefront turns each strip of
+  // 64 layer rows x 16 x rows through LDS (its own region, over the tiles that are no longer needed; LDS
+  // accesses of one wavefront complete in order) and writes, or adds, 64 consecutive floats per x row.
+  constexpr int kStageStride = 65;
+  static_assert(4 * 16 * kStageStride * sizeof(float) <= sizeof(sm.a) + sizeof(sm.b), "staging fits the tiles");
+  float* stage = reinterpret_cast<float*>(&sm.a[0][0]) + wave * (16 * kStageStride);
+  const int nn = n_base + wn + lane;
 #pragma unroll
   for (int j = 0; j < kMJ; ++j) {
-    const int mm = m_base + wm + 16 * j + r;
-    if (mm >= M) continue;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int nn = n_base + wn + 16 * i + 4 * q + e;
-        if (nn < N) y[(int64_t)mm * ldy + nn] = acc[i][j][e];
+      for (int e = 0; e < 4; ++e) stage[r * kStageStride + 16 * i + 4 * q + e] = acc[i][j][e];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int mr = 0; mr < 16; ++mr) {
+      const int mm = m_base + wm + 16 * j + mr;
+      const float v = stage[mr * kStageStride + lane];
+      if (mm < M && nn < N) {
+        if (gridDim.z == 1) y[(int64_t)mm * ldy + nn] = v;
+        else atomicAdd(&y[(int64_t)mm * ldy + nn], v);
       }
+    }
+    __builtin_amdgcn_wave_barrier();
   }
+}
+
+// y[0 .. M)[0 .. N) = 0, for products whose blocks add their parts into y
+__global__ void clear_y_kernel(float* __restrict__ y, int64_t ldy, int M, int N) {
+  const int64_t total = (int64_t)M * N;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x)
+    y[(e / N) * ldy + e % N] = 0.0f;
 }
 
 int log2i(int v) {
@@ -546,12 +570,22 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   // Few rows: per pass 9 us + 0.2 ps per weight.
   const double work = (double)N * (double)K;
   const int64_t n_tiles = (N + kTileN - 1) / kTileN;
+  // With fewer tiles than compute units a block would walk all of K alone at the one-block stage time;
+  // K is then split over blockIdx.z (parts added into y with atomics, y cleared first: about 3 us more)
+  // until the blocks fill the compute units once, each part keeping at least 8 stages.
+  const auto k_parts = [&](int bm) {
+    const int64_t tiles = n_tiles * ((M + bm - 1) / bm);
+    int64_t parts = cus / tiles;
+    if (parts > K / kTileK / 8) parts = K / kTileK / 8;
+    return (int)(parts < 1 ? 1 : parts);
+  };
   const auto tiled_us = [&](int bm, const double* per_stage, int fit) {
-    const int64_t blocks = n_tiles * ((M + bm - 1) / bm), per_round = (int64_t)cus * fit;
+    const int parts = k_parts(bm);
+    const int64_t blocks = n_tiles * ((M + bm - 1) / bm) * parts, per_round = (int64_t)cus * fit;
     const int64_t full = blocks / per_round, rem = blocks % per_round;
     double t = (double)full * per_stage[fit - 1];
     if (rem > 0) t += per_stage[(rem + cus - 1) / cus - 1];
-    return t * (double)(K / kTileK);
+    return t * (double)(K / kTileK) / parts + (parts > 1 ? 3.0 : 0.0);
   };
   static const double kNarrowStage[3] = {1.33, 1.95, 2.6}, kWideStage[2] = {2.0, 3.0};
   const double narrow_us = tiled_us(128, kNarrowStage, 3), wide_us = tiled_us(256, kWideStage, 2);
@@ -559,7 +593,14 @@ hipError_t launch_gemm_w4a16(const void* x, int64_t M, int64_t ldx, const uint8_
   if (M > 64 && (narrow_us < rows_us || wide_us < rows_us)) {
     const bool wide = wide_us < narrow_us;
     const int bm = wide ? 256 : 128;
-    const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm));
+    const int parts = k_parts(bm);
+    if (parts > 1) {
+      const int64_t want = ((int64_t)M * N + 1023) / 1024;
+      clear_y_kernel<<<(unsigned)(want < 2048 ? want : 2048), 256, 0, stream>>>(y, ldy, (int)M, (int)N);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    const dim3 grid((unsigned)n_tiles, (unsigned)((M + bm - 1) / bm), (unsigned)parts);
 #define AAAC_TILED(FMT, BM, GS, SEL)                                                                              \
   gemm_w4a16_tiled_kernel<FMT, BM, GS, SEL><<<grid, kTiledBlock, 0, stream>>>(                                     \
       xp, ldx, (int)M, codes, scales, bits, sel_stride, tables_bf16, (int)N, (int)K, log2i(group_size),          \

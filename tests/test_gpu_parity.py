@@ -832,6 +832,8 @@ def oracle_args(x, codes, scales, bits, tb, fmt):
     (128, 1024, 128, 16, 1, 256),   # tiled, selection bits from the bit array
     (77, 640, 32, 32, 1, 65),       # tiled, one partial tile each way
     (260, 2048, 16, 16, 1, 200),    # tiled, bf16 scales with groups of 16
+    (256, 8192, 16, 16, 0, 256),    # tiled, two tiles only: K split over 16 blocks each, parts added in y
+    (200, 4096, 128, 32, 1, 100),   # tiled, ragged tiles with K split over 8 blocks, selection bits
 ])
 def test_gemm_w4a16_exact_on_integer_data_and_bounded_on_real_data(N, K, g, S, fmt, M):
     say(f"[gemm] N={N} K={K} g={g} S={S} fmt={fmt} M={M}")
