@@ -372,7 +372,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=4, help="index into the five benchmark settings")
+    ap.add_argument("--config", type=int, default=None,
+                    help="index into the five benchmark settings (default: 4, the largest, with the smaller ones "
+                         "measured too and reported as per_config)")
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the measurement of the smaller settings that the default run adds as per_config")
     ap.add_argument("--n-inner", type=int, default=1,
@@ -399,8 +401,10 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    out = measure(args, args.config, args.steps, args.warmup, cpu_baseline=not args.no_cpu_baseline, extras=True)
-    plain = (args.n_inner == 1 and args.sel_size is None and not args.quantile_init and args.config == 4)
+    config = 4 if args.config is None else args.config
+    out = measure(args, config, args.steps, args.warmup, cpu_baseline=not args.no_cpu_baseline, extras=True)
+    plain = (args.config is None and args.n_inner == 1 and args.sel_size is None and not args.quantile_init
+             and args.gemv_rows == 0 and args.gemm_rows == 0)
     if plain and not args.no_per_config:
         # the smaller settings in the same run: same kind of step, their own inputs, fewer details
         per = {}
