@@ -87,7 +87,12 @@ def measured_counters(workload):
         data = json.load(f)
     if data.get("kernel_source_hash") != kernel_source_hash():
         return None
-    return data.get("workloads", {}).get(workload)
+    w = data.get("workloads", {}).get(workload)
+    if w is None:
+        return None
+    keep = ("kernel", "launches_averaged", "weights_per_launch", "executed_lane_ops_per_weight", "valu_busy", "lds_busy",
+            "lds_instructions_per_weight", "hbm_bytes_per_launch", "algorithmic_bytes_per_launch")
+    return {k: w[k] for k in keep if k in w}
 
 
 def measure(args, cfg_id, steps_arg, warmup_arg, cpu_baseline, extras):

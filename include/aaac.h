@@ -105,7 +105,16 @@ int aaac_act_stats_static(const void* X, int64_t tokens, int64_t K, int64_t ldx,
  *   objective_trace dev fp64 [iterations] or NULL: sum over groups of min(e0, e1)
  *                as seen by each assignment step
  *   ws           dev scratch, >= aaac_fit_workspace(N, K, group_size, fmt) bytes
- * N == 0 is allowed (tables stay at init_grid). */
+ * N == 0 is allowed (tables stay at init_grid).
+ * How the passes are launched does not change what is computed: a single small layer
+ * (at most 512 rows of 512-column strips) runs all its passes in one launch whose blocks
+ * exchange partial sums and add them in a fixed order; larger layers and batches take
+ * one launch per pass, with fp64 sums added in arrival order (results may differ between
+ * runs in the last bits of an fp64 sum).  The environment variable AAAC_FIT_PATH, read at
+ * every call, overrides the choice for measurements and tests: "launches" never takes
+ * the one-launch path, "persistent" takes it for every single layer it can hold (2048
+ * rows of strips).  If the blocks of a one-launch fit cannot exchange their sums within
+ * about four seconds (a device kept busy by other work), the tables come back as NaN. */
 size_t aaac_fit_workspace(int64_t N, int64_t K, int group_size, aaac_format_t fmt);
 int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,
              const float* importance, const float* init_grid, int iterations, float* tables_f32,
