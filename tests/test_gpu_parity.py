@@ -289,10 +289,29 @@ def test_fit_is_repeatable_and_resumable():
     assert (u16(a[1]) == u16(r[1])).all() and np.allclose(host(a[0]), host(r[0]), rtol=1e-6)
 
 
-def test_whole_path_can_be_captured_in_a_graph_and_replayed():
+def test_one_launch_fit_is_the_same_bit_for_bit_on_every_run():
+    """The one-launch path adds the blocks' partial sums in block order, whatever the timing: fp32 tables
+    and the objective trace repeat exactly (the launch-per-pass path only promises the last bits of an
+    fp64 sum away)."""
+    Wt = inputs.make_weight(200, 512, "gauss_outlier", 12, DEV)
+    I = torch.rand(512, device=DEV, generator=seeded(11030)) + 0.1
+    with fit_path("persistent"):
+        runs = [A.aaac_fit(Wt, 16, 0, I, inputs.format_grid(0), 7) for _ in range(4)]
+        torch.cuda.synchronize()
+    for tf, tb, ob in runs[1:]:
+        assert torch.equal(tf, runs[0][0]) and torch.equal(tb, runs[0][1]) and torch.equal(ob, runs[0][2])
+
+
+@pytest.mark.parametrize("path", FIT_PATHS)
+def test_whole_path_can_be_captured_in_a_graph_and_replayed(path):
     """The library only launches kernels (no memset or memcpy nodes), so a caller may
-    capture it; every replay must give the eager result, also after other work."""
-    N, K, g, fmt, iters = 512, 1024, 16, 0, 4
+    capture it; every replay must give the eager result, also after other work.  With
+    "persistent" the captured fit is the one-launch kernel whose blocks wait for each other."""
+    with fit_path(path):   # read by the library when the calls are made, i.e. at capture
+        whole_path_in_a_graph(*((512, 1024, 16, 0, 4) if path == "launches" else (256, 512, 16, 0, 4)))
+
+
+def whole_path_in_a_graph(N, K, g, fmt, iters):
     Wt = inputs.make_weight(N, K, "gauss_outlier", 21, DEV)
     X = inputs.make_activations(256, K, ("gauss", 0.01, "u10_50"), 22, DEV)
     grid = inputs.format_grid(fmt)
