@@ -23,6 +23,7 @@
 #include <type_traits>
 #include "aaac_device.h"
 #include "aaac_internal.h"
+#include "aaac_stream.h"
 
 namespace aaac {
 
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(kGemvBlock) __attribute__((amdgpu_waves_per_eu(MB >
         for (int u = 0; u < kRowsInFlight; ++u) {
           const int row0 = base + u * row_step;
           const int row = row0 < r1 ? row0 : r1 - 1;
-          rr[u].c = *reinterpret_cast<const uint4*>(cbase + (int64_t)row * row_bytes);
+          rr[u].c = load_once_16(cbase + (int64_t)row * row_bytes);
           const int64_t g = (int64_t)row * Gs + sidx;
           if (FMT == 0) {
             if (G16) rr[u].sc = *reinterpret_cast<const uint16_t*>(static_cast<const uint8_t*>(scales) + g);
