@@ -166,7 +166,8 @@ int aaac_fit_nested(const aaac_layer_t* layers, int n_layers, int group_size, in
  * is taken by linear interpolation between order statistics x_(0) <= ... <= x_(n-1):
  * with lo = num*(n-1) div den and rem = num*(n-1) mod den (exact integers),
  * value = fl32( x_(lo) + (rem/den) * (x_(lo+1) - x_(lo)) ) evaluated in fp64; a zero is
- * stored as +0.  The order statistics are exact (radix select, no sampling).
+ * stored as +0.  The order statistics are exact (radix select, no sampling; three passes
+ * over the weights and one over the keys that can still matter, kept in ws).
  *   grid   dev fp32 [32], overwritten: T0[0..15] then T1[0..15], each ascending
  *   ws     dev scratch of aaac_quantile_init_workspace(...) bytes, 256-byte aligned
  * N = 0 or K = 0 is AAAC_ERR_SHAPE (no weights to take quantiles of); other errors as

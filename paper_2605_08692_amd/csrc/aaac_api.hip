@@ -156,7 +156,9 @@ int aaac_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int gro
   float* rinv = reinterpret_cast<float*>(base + p.off_rinv);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (aaac::launch_group_rinv(W, N, K, ldw, group_size, fmt, rinv, stream) != hipSuccess) return AAAC_ERR_HIP;
-  return from_hip(aaac::launch_quantile_init(W, N, K, ldw, group_size, rinv, base + p.off_quant, grid, stream));
+  return from_hip(aaac::launch_quantile_init(W, N, K, ldw, group_size, rinv, base + p.off_quant,
+                                             reinterpret_cast<uint32_t*>(base + p.off_cand),
+                                             aaac::quant_candidates(N, K), grid, stream));
 }
 
 int aaac_fit(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size, aaac_format_t fmt,

@@ -26,6 +26,9 @@ constexpr int kQuantSlots = 64;  // distinct key prefixes followed at once = wan
 struct QuantState {
   unsigned long long hist1[4096];              // pass 1: counts per top 12 key bits
   unsigned long long hist[kQuantSlots][256];   // passes 2-4: counts per slot and next key bits
+  uint32_t cand_count[256];                    // keys that block b of pass 3 put on its part of the candidate list
+  uint32_t cand_overflow;                      // non-zero: some key did not fit, pass 4 reads the weights again
+  uint32_t cand_pad;
   uint8_t map1[4096];                          // top 12 bits -> slot of pass 2 (0xFF: not followed)
   uint8_t map2[kQuantSlots][256];              // slot of pass 2, next 8 bits -> slot of pass 3
   uint8_t map3[kQuantSlots][256];              // slot of pass 3, next 8 bits -> slot of pass 4
@@ -45,8 +48,15 @@ struct QuantTargets {  // passed to kernels by value
 };
 QuantTargets make_quant_targets(int64_t N, int64_t K);
 // rinv: the reciprocal scales of the layer (launch_group_rinv) must be enqueued before.
+// cand: room for cand_cap 32-bit keys (the keys that still matter after three passes; see quant_candidates).
 hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size,
-                                const float* rinv, void* quant_state, float* grid_out, hipStream_t stream);
+                                const float* rinv, void* quant_state, uint32_t* cand, int64_t cand_cap,
+                                float* grid_out, hipStream_t stream);
+// Keys the candidate list of a layer has room for: one in 32 weights, at least 16384.
+inline int64_t quant_candidates(int64_t N, int64_t K) {
+  const int64_t n = (N > 0 ? N : 0) * (K > 0 ? K : 0) / 32;
+  return n < 16384 ? 16384 : n;
+}
 
 // How a layer is cut into blocks for the Lloyd iteration: a block owns a
 // rectangle of `strips_per_block` 512-column strips x `rows_per_block` rows.
@@ -65,7 +75,7 @@ FitPlan make_fit_plan(int64_t N, int64_t K, int64_t ldw, int group_size, int sel
 
 // Byte offsets of the parts of a layer's fit workspace; depends on the shape only (no device query).
 struct FitLayout {
-  size_t off_state, off_rinv, off_sigma, off_quant, off_small, bytes;
+  size_t off_state, off_rinv, off_sigma, off_quant, off_cand, off_small, bytes;
 };
 FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size);
 

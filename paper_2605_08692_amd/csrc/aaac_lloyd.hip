@@ -380,7 +380,8 @@ FitLayout fit_layout(int64_t N, int64_t K, int group_size, int sel_size) {
   const size_t groups = (size_t)(N > 0 ? N : 0) * (K / group_size);
   p.off_sigma = p.off_rinv + align(groups * sizeof(float));
   p.off_quant = p.off_sigma + align((size_t)(N > 0 ? N : 0) * (K / sel_size));  // one byte per selection group
-  p.off_small = p.off_quant + align(sizeof(QuantState));
+  p.off_cand = p.off_quant + align(sizeof(QuantState));
+  p.off_small = p.off_cand + align((size_t)quant_candidates(N, K) * sizeof(uint32_t));
   p.bytes = p.off_small + align(kSmallStateBytes);
   return p;
 }
@@ -441,7 +442,9 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
         float* rinv = reinterpret_cast<float*>(base + lay.off_rinv);
         hipError_t e = launch_group_rinv(t.W, t.N, t.K, t.ldw, group_size, fmt, rinv, stream);
         if (e != hipSuccess) return e;
-        e = launch_quantile_init(t.W, t.N, t.K, t.ldw, group_size, rinv, qs, qs->grid, stream);
+        e = launch_quantile_init(t.W, t.N, t.K, t.ldw, group_size, rinv, qs,
+                                 reinterpret_cast<uint32_t*>(base + lay.off_cand), quant_candidates(t.N, t.K),
+                                 qs->grid, stream);
         if (e != hipSuccess) return e;
       }
       return launch_fit_small(t, sp, group_size, sel_size, fmt, grid, qs->grid,
@@ -452,6 +455,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
   // that hold weights take part in the iterations
   BatchArgs all = {}, work = {};
   QuantState* quant[kMaxFusedLayers] = {};  // of the layers in `work`
+  uint32_t* cand[kMaxFusedLayers] = {};     // their candidate lists
   for (int g = group_size; g > 1; g >>= 1) ++work.gshift;
   double total = 0.0;
   for (int i = 0; i < n; ++i) total += (double)tasks[i].N * (double)tasks[i].K;
@@ -525,6 +529,7 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
       a.block_begin = blocks;
       blocks += p.blocks;
       quant[work.n] = qs;
+      cand[work.n] = reinterpret_cast<uint32_t*>(base + lay.off_cand);
       work.layer[work.n++] = a;
     }
   }
@@ -536,7 +541,8 @@ hipError_t launch_fit_group(const FitTask* tasks, int n, int group_size, int sel
       e = launch_group_rinv(a.W, a.N, a.K, a.ldw, group_size, fmt, const_cast<float*>(a.rinv), stream);
       if (e != hipSuccess) return e;
       if (!grid) {
-        e = launch_quantile_init(a.W, a.N, a.K, a.ldw, group_size, a.rinv, quant[i], quant[i]->grid, stream);
+        e = launch_quantile_init(a.W, a.N, a.K, a.ldw, group_size, a.rinv, quant[i], cand[i],
+                                 quant_candidates(a.N, a.K), quant[i]->grid, stream);
         if (e != hipSuccess) return e;
       }
     }

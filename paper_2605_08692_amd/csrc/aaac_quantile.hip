@@ -37,24 +37,44 @@ template <> struct PassBits<2> { static constexpr int shift = 12, bins = 256; };
 template <> struct PassBits<3> { static constexpr int shift = 4, bins = 256; };
 template <> struct PassBits<4> { static constexpr int shift = 0, bins = 16; };
 
+constexpr int kWaveQueue = 512;   // keys a wavefront can hold before it moves them to the candidate list
+constexpr int kQueueMove = 256;   // it moves them when it holds this many (looked at once per 32 weights of a lane)
+
 struct QuantLds {
   uint32_t hist[kQuantSlots * 256];  // pass 1 uses the first 4096 counters
   uint8_t map1[4096];
   uint8_t map2[kQuantSlots][256];
   uint8_t map3[kQuantSlots][256];
+  uint32_t queue[kQBlock / 64][kWaveQueue];  // pass 3: the keys each wavefront has found and not yet moved
+  uint32_t queued[kQBlock / 64];             // how many
+  uint32_t listed;                           // keys the block has moved to its part of the list
 };
 
 // One histogram pass.  The matrix is cut into 16-byte chunks (8 weights); block b
 // owns chunks [b * per_block, (b + 1) * per_block), a thread takes every 1024th.
+//
+// Pass 3 also writes every key it counts (a key whose first 20 bits some wanted rank still follows:
+// one weight in sixty or fewer) to the candidate list, and pass 4 then reads that list instead of
+// the weights.  Block b owns part b of the list (no global atomics: thousands of them on one counter
+// cost more than the pass); a wavefront collects its keys in LDS (position from an LDS atomic, which
+// only the few lanes with such a key execute) and moves them to the block's part when it holds 256.
+// Keys that find the wavefront's queue or the block's part full (many equal weights) are dropped and
+// cand_overflow is set: pass 4 then reads the weights like the other passes.
 template <int PASS>
 __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __restrict__ W,
                                                              const float* __restrict__ rinv, int64_t N, int K,
                                                              int64_t ldw, int gshift, int64_t per_block,
-                                                             QuantState* __restrict__ qs) {
+                                                             QuantState* __restrict__ qs, uint32_t* __restrict__ cand,
+                                                             const unsigned long long cand_cap) {
   __shared__ QuantLds sm;
   constexpr int kCounters = PASS == 1 ? 4096 : kQuantSlots * PassBits<PASS>::bins;
-  const int tid = threadIdx.x;
+  constexpr uint32_t kBins = PassBits<PASS>::bins;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < kCounters; i += kQBlock) sm.hist[i] = 0u;
+  if (tid < kQBlock / 64) sm.queued[tid] = 0u;
+  if (tid == 0) sm.listed = 0u;
+  const uint32_t part_cap = (uint32_t)(cand_cap / gridDim.x < 0xFFFFFFFFull ? cand_cap / gridDim.x : 0xFFFFFFFFull);
+  uint32_t* const part = cand + (size_t)blockIdx.x * part_cap;
   if (PASS >= 2)
     for (int i = tid; i < 4096 / 4; i += kQBlock)
       reinterpret_cast<uint32_t*>(sm.map1)[i] = reinterpret_cast<const uint32_t*>(qs->map1)[i];
@@ -66,63 +86,132 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
       reinterpret_cast<uint32_t*>(&sm.map3[0][0])[i] = reinterpret_cast<const uint32_t*>(&qs->map3[0][0])[i];
   __syncthreads();
 
-  const int cpr = K / 8;  // chunks per row
-  const int Gs = K >> gshift;
-  const int64_t total = N * (int64_t)cpr;
-  const int64_t begin = (int64_t)blockIdx.x * per_block;
-  int64_t end = begin + per_block;
-  if (end > total) end = total;
-  int64_t e = begin + tid;
-  int64_t row = e / cpr;
-  int c = (int)(e - row * cpr);
-  const int step_rows = kQBlock / cpr, step_c = kQBlock % cpr;
-  // Four chunks are asked for together (a thread has few chunks, and waiting for each before asking
-  // for the next left the pass bound by memory latency); the loads are unconditional, a chunk beyond
-  // the block's range reads the batch's first chunk again and is not counted.
-  constexpr int kBatch = 4;
-  for (; e < end; e += kBatch * kQBlock) {
-    int64_t rows[kBatch];
-    int cs[kBatch];
+  // Counts the 8 keys of a lane (bit p of valid: key p is to be counted).  The look-ups of the 8 keys
+  // go out together; a key that is not followed (0xFF) reads the next map at slot 63 and drops what
+  // it finds.
+  uint32_t* const queue = sm.queue[wave];
+  bool dropped = false;
+  auto count_keys = [&](const uint32_t (&key)[8], const uint32_t valid) {
+    if (PASS == 1) {
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      rows[u] = row;
-      cs[u] = c;
-      row += step_rows;
-      c += step_c;
-      if (c >= cpr) { c -= cpr; ++row; }
+      for (int p = 0; p < 8; ++p)
+        if ((valid >> p) & 1u) atomicAdd(&sm.hist[key[p] >> 20], 1u);
+      return;
     }
-    uint4 v[kBatch];
-    float r[kBatch];
+    uint32_t slot[8];
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const bool ok = e + (int64_t)u * kQBlock < end;
-      const int64_t ru = ok ? rows[u] : rows[0];
-      const int col = (ok ? cs[u] : cs[0]) * 8;
-      v[u] = *reinterpret_cast<const uint4*>(W + ru * ldw + col);
-      r[u] = rinv[ru * Gs + (col >> gshift)];
+    for (int p = 0; p < 8; ++p) slot[p] = sm.map1[key[p] >> 20];
+    if (PASS >= 3) {
+      uint32_t next[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) next[p] = sm.map2[slot[p] & 63u][(key[p] >> 12) & 0xFFu];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) slot[p] = slot[p] == 0xFFu ? 0xFFu : next[p];
+    }
+    if (PASS >= 4) {
+      uint32_t next[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) next[p] = sm.map3[slot[p] & 63u][(key[p] >> 4) & 0xFFu];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) slot[p] = slot[p] == 0xFFu ? 0xFFu : next[p];
     }
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (e + (int64_t)u * kQBlock >= end) break;
-      const W8 w = unpack8(v[u]);
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const uint32_t key = order_key(w.w[p] * r[u]);
-        if (PASS == 1) {
-          atomicAdd(&sm.hist[key >> 20], 1u);
-        } else {
-          uint32_t s = sm.map1[key >> 20];
-          if (PASS >= 3 && s != 0xFFu) s = sm.map2[s][(key >> 12) & 0xFFu];
-          if (PASS >= 4 && s != 0xFFu) s = sm.map3[s][(key >> 4) & 0xFFu];
-          if (s != 0xFFu) {
-            const uint32_t bin = (key >> PassBits<PASS>::shift) & (uint32_t)(PassBits<PASS>::bins - 1);
-            atomicAdd(&sm.hist[s * PassBits<PASS>::bins + bin], 1u);
-          }
+    for (int p = 0; p < 8; ++p) {
+      if (((valid >> p) & 1u) && slot[p] != 0xFFu) {
+        atomicAdd(&sm.hist[slot[p] * kBins + ((key[p] >> PassBits<PASS>::shift) & (kBins - 1u))], 1u);
+        if (PASS == 3) {
+          const uint32_t at = atomicAdd(&sm.queued[wave], 1u);
+          if (at < (uint32_t)kWaveQueue) queue[at] = key[p];
+          else dropped = true;
         }
       }
     }
+  };
+  // Moves the wavefront's keys to the block's part of the list when it holds `least` or more; all 64
+  // lanes call it together.
+  auto move_queue = [&](const uint32_t least) {
+    __builtin_amdgcn_wave_barrier();
+    uint32_t n = sm.queued[wave];  // one address: the same value in every lane
+    if (n < least || n == 0u) return;
+    if (n > (uint32_t)kWaveQueue) n = kWaveQueue;
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&sm.listed, n);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (uint32_t i = lane; i < n; i += 64)
+      if (base + i < part_cap) part[base + i] = queue[i];
+    if (base + n > part_cap) dropped = true;
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) sm.queued[wave] = 0u;
+    __builtin_amdgcn_wave_barrier();
+  };
+
+  if (PASS == 4 && qs->cand_overflow == 0u) {
+    // the candidate list holds every key that can still matter (this block reads the part that the
+    // block of the same number wrote: both passes run the same grid); a thread takes 8 keys at a time
+    const uint32_t n = qs->cand_count[blockIdx.x];  // <= part_cap
+    for (uint32_t i = (uint32_t)tid * 8u; i < n; i += kQBlock * 8u) {
+      uint32_t key[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) key[p] = part[i + p < n ? i + p : i];
+      const uint32_t left = n - i;  // a key past the end repeats key i and is not counted
+      count_keys(key, left >= 8u ? 0xFFu : (1u << left) - 1u);
+    }
+  } else {
+    const int cpr = K / 8;  // chunks per row
+    const int Gs = K >> gshift;
+    const int64_t total = N * (int64_t)cpr;
+    const int64_t begin = (int64_t)blockIdx.x * per_block;
+    int64_t end = begin + per_block;
+    if (end > total) end = total;
+    int64_t e = begin + tid;
+    int64_t row = e / cpr;
+    int c = (int)(e - row * cpr);
+    const int step_rows = kQBlock / cpr, step_c = kQBlock % cpr;
+    // Four chunks are asked for together (a thread has few chunks, and waiting for each before asking
+    // for the next left the pass bound by memory latency); the loads are unconditional, a chunk beyond
+    // the block's range reads the batch's first chunk again (the layer's first, when that is beyond
+    // the range too) and is not counted.  The loop runs the same number of times in every lane of a
+    // wavefront, because in pass 3 the lanes move their keys to the list together.
+    constexpr int kBatch = 4;
+    for (int64_t we = begin + (tid & ~63); we < end; we += kBatch * kQBlock, e += kBatch * kQBlock) {
+      int64_t rows[kBatch];
+      int cs[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        rows[u] = row;
+        cs[u] = c;
+        row += step_rows;
+        c += step_c;
+        if (c >= cpr) { c -= cpr; ++row; }
+      }
+      uint4 v[kBatch];
+      float r[kBatch];
+      bool ok[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        ok[u] = e + (int64_t)u * kQBlock < end;
+        const int64_t ru = ok[u] ? rows[u] : (ok[0] ? rows[0] : 0);
+        const int col = (ok[u] ? cs[u] : (ok[0] ? cs[0] : 0)) * 8;
+        v[u] = *reinterpret_cast<const uint4*>(W + ru * ldw + col);
+        r[u] = rinv[ru * Gs + (col >> gshift)];
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const W8 w = unpack8(v[u]);
+        uint32_t key[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p) key[p] = order_key(w.w[p] * r[u]);
+        count_keys(key, ok[u] ? 0xFFu : 0u);
+      }
+      if (PASS == 3) move_queue(kQueueMove);
+    }
+    if (PASS == 3) {
+      move_queue(1u);
+      if (dropped) qs->cand_overflow = 1u;
+    }
   }
   __syncthreads();
+  if (PASS == 3 && tid == 0) qs->cand_count[blockIdx.x] = sm.listed < part_cap ? sm.listed : part_cap;
   unsigned long long* out = PASS == 1 ? qs->hist1 : &qs->hist[0][0];
   for (int i = tid; i < kCounters; i += kQBlock) {
     const uint32_t n = sm.hist[i];
@@ -351,7 +440,8 @@ QuantTargets make_quant_targets(int64_t N, int64_t K) {
 }
 
 hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw, int group_size,
-                                const float* rinv, void* quant_state, float* grid_out, hipStream_t stream) {
+                                const float* rinv, void* quant_state, uint32_t* cand, int64_t cand_cap,
+                                float* grid_out, hipStream_t stream) {
   QuantState* qs = static_cast<QuantState*>(quant_state);
   const uint16_t* Wp = static_cast<const uint16_t*>(W);
   int gshift = 0;
@@ -366,7 +456,8 @@ hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw
   const int64_t per_block = ceil_div(ceil_div(chunks, blocks), kQBlock) * kQBlock;
   blocks = ceil_div(chunks, per_block);
 #define AAAC_QPASS(P)                                                                                          \
-  quant_hist_kernel<P><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, qs); \
+  quant_hist_kernel<P><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, qs, \
+                                                                 cand, (unsigned long long)cand_cap);          \
   if ((e = hipGetLastError()) != hipSuccess) return e;                                                         \
   quant_select_kernel<P><<<1, kQBlock, 0, stream>>>(qs, tg, grid_out);                                         \
   if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -35,7 +35,9 @@ int main() {
           CHECK(lay.off_rinv % 256 == 0 && lay.off_sigma % 256 == 0 && lay.off_quant % 256 == 0 && lay.off_small % 256 == 0);
           CHECK(lay.off_sigma - lay.off_rinv >= (size_t)N * (K / g) * sizeof(float));
           CHECK(lay.off_quant - lay.off_sigma >= (size_t)N * (K / s));
-          CHECK(lay.off_small - lay.off_quant >= sizeof(QuantState));
+          CHECK(lay.off_cand % 256 == 0 && lay.off_cand - lay.off_quant >= sizeof(QuantState));
+          CHECK(quant_candidates(N, K) >= 16384 && quant_candidates(N, K) >= N * K / 32);
+          CHECK(lay.off_small - lay.off_cand >= (size_t)quant_candidates(N, K) * sizeof(uint32_t));
           CHECK(lay.bytes - lay.off_small >= kSmallStateBytes && lay.bytes % 256 == 0);
         }
         for (int c : cu_counts) {

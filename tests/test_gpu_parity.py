@@ -638,6 +638,15 @@ def test_quantile_init_degenerate_weights_and_padded_rows():
     grid = A.aaac_quantile_init(Wt, 128, A.INT4)
     torch.cuda.synchronize()
     assert (u32(host(grid)) == u32(oracle.quantile_init(inputs.bits(Wt), 128, A.INT4))).all()
+    # a few distinct values in a layer of half a million weights: far more keys share the followed
+    # prefixes than the candidate list of the radix select holds, so its last pass reads the weights
+    vals = torch.tensor([-0.07, -0.02, 0.0, 0.013, 0.05], device=DEV)
+    for g, fmt in ((16, A.NVFP4), (128, A.INT4)):
+        pick = torch.randint(0, 5, (512, 1024), device=DEV, generator=seeded(11011 + g))
+        Wt = vals[pick].to(torch.bfloat16)
+        grid = A.aaac_quantile_init(Wt, g, fmt)
+        torch.cuda.synchronize()
+        assert (u32(host(grid)) == u32(oracle.quantile_init(inputs.bits(Wt), g, fmt))).all()
     # rows with a padded leading dimension; the padding holds large values that must not be read
     big = torch.full((50, 768), 100.0, dtype=torch.bfloat16, device=DEV)
     Wp = big[:, :640]
