@@ -211,8 +211,11 @@ def measure(args, cfg_id, steps_arg, warmup_arg, cpu_baseline, extras):
         e1.record(stream)
         torch.cuda.synchronize()
         q_ms = e0.elapsed_time(e1) / 5
+        # the scale kernel (reads W, writes one fp32 per group) and three histogram passes (read both) touch the
+        # weights; the fourth pass of the radix select reads the short candidate list
         q_gbs = 4 * bytes_per_weight(g) * n_w / (q_ms * 1e-3) / 1e9
-        quant = {"ms": q_ms, "passes_over_weights": 4, "hbm_achieved_GBs": q_gbs, "hbm_frac": q_gbs / HBM_PEAK_GBS}
+        quant = {"ms": q_ms, "passes_over_weights": 4, "of_which_scale_kernel": 1, "hbm_achieved_GBs": q_gbs,
+                 "hbm_frac": q_gbs / HBM_PEAK_GBS}
         iter_us = (fit_ms - q_ms) * 1e3 / passes
         weights_per_s_iter = n_w / (iter_us * 1e-6)
 
