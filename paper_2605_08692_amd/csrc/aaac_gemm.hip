@@ -328,7 +328,7 @@ void gemm_w4a16_tiled_kernel(
     for (int j = 0; j < kMJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // What a thread loads per stage: 16 code bytes, the raw scale codes (taken apart where they are used) and
-  // selection byte, 32 activations of one or two x rows.  The loads are unconditional, from clamped
+  // selection byte, four or eight units of 8 activations.  The loads are unconditional, from clamped
   // addresses: a layer row beyond N reads row N - 1 and an x row beyond M reads row M - 1 (their outputs
   // are not stored), the stage after the last reads the last stage again (never used).
   struct StageRegs {
@@ -338,11 +338,16 @@ void gemm_w4a16_tiled_kernel(
   };
   const int n_load = has_n ? n : N - 1;
   const uint8_t* crow_load = codes + (int64_t)n_load * (K / 2);
-  const uint16_t* xrow[kXRows];
+  // x: load j of a thread is unit tid & 7 (8 columns) of row 32 j + tid / 8 of the block's x tile, so that
+  // 8 consecutive lanes read one 128-byte line of x (with the weights' mapping, two lanes per row, a load
+  // touched 32 lines for 32 bytes each: 2-9 % slower)
+  constexpr int kXLoads = kXRows * 4;
+  const int xunit = tid & 7, xr0 = tid >> 3;
+  const uint16_t* xrow[kXLoads];
 #pragma unroll
-  for (int xr = 0; xr < kXRows; ++xr) {
-    const int m = m_base + lrow + 128 * xr;
-    xrow[xr] = x + (int64_t)(m < M ? m : M - 1) * ldx;
+  for (int j = 0; j < kXLoads; ++j) {
+    const int m = m_base + 32 * j + xr0;
+    xrow[j] = x + (int64_t)(m < M ? m : M - 1) * ldx + 8 * xunit;
   }
   auto fetch = [&](StageRegs& sr, int k_stage) {
     const int k0 = (k_stage < K ? k_stage : K - kTileK) + 32 * half;
@@ -356,10 +361,9 @@ void gemm_w4a16_tiled_kernel(
                        : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
     sr.selbyte = 0;
     if (SEL) sr.selbyte = sel_bits[(int64_t)n_load * sel_stride + ((k0 >> sshift) >> 3)];
+    const int kx = k_stage < K ? k_stage : K - kTileK;
 #pragma unroll
-    for (int xr = 0; xr < kXRows; ++xr)
-#pragma unroll
-      for (int u = 0; u < 4; ++u) sr.xv[4 * xr + u] = *reinterpret_cast<const u32x4*>(xrow[xr] + k0 + 8 * u);
+    for (int j = 0; j < kXLoads; ++j) sr.xv[j] = *reinterpret_cast<const u32x4*>(xrow[j] + kx);
   };
   // blockIdx.z: which part of K this block sums (stages of 64 columns; with more than one part the
   // parts are added into y, which the host has cleared)
@@ -391,10 +395,10 @@ void gemm_w4a16_tiled_kernel(
       }
       const int unit = (4 * half + u) ^ (lrow & 7);
       sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
-#pragma unroll
-      for (int xr = 0; xr < kXRows; ++xr)  // rows 128 apart have the same row & 7
-        *reinterpret_cast<u32x4*>(&sm.b[lrow + 128 * xr][unit]) = sr.xv[4 * xr + u];
     }
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j)  // rows 32 apart have the same row & 7
+      *reinterpret_cast<u32x4*>(&sm.b[32 * j + xr0][xunit ^ (xr0 & 7)]) = sr.xv[j];
     __syncthreads();
     // the next stage's loads are in flight during the matrix instructions (the empty statements keep the
     // compiler from moving them below)
