@@ -3,10 +3,11 @@
 // normalised weights of a layer, linear interpolation between order statistics.
 //
 // The order statistics are found exactly, without sorting, by a radix select over
-// the order-preserving 32-bit key of w~ = w * (1/s): four passes over the weights
-// (12 + 8 + 8 + 4 key bits), each a histogram in LDS (merged into global memory
-// with 64-bit atomics), each followed by a one-block kernel that walks the
-// histogram for all wanted ranks at once.  At most 64 ranks are wanted (32
+// the order-preserving 32-bit key of w~ = w * (1/s): four passes (12 + 8 + 8 + 4
+// key bits), the first three over the weights and the last over the short list of
+// keys that the third found still to matter, each a histogram in LDS (merged into
+// global memory with 64-bit atomics), each followed by a one-block kernel that
+// walks the histogram for all wanted ranks at once.  At most 64 ranks are wanted (32
 // quantiles, two neighbouring order statistics each); after a pass, the ranks
 // that still share a key prefix share a "slot", and the next pass only counts
 // keys whose prefix has a slot, looked up through small tables in LDS.
