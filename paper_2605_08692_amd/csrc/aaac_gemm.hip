@@ -361,6 +361,8 @@ void gemm_w4a16_tiled_kernel(
                        : (uint32_t) static_cast<const uint16_t*>(scales)[g0];
     sr.selbyte = 0;
     if (SEL) sr.selbyte = sel_bits[(int64_t)n_load * sel_stride + ((k0 >> sshift) >> 3)];
+  };
+  auto fetch_x = [&](StageRegs& sr, int k_stage) {
     const int kx = k_stage < K ? k_stage : K - kTileK;
 #pragma unroll
     for (int j = 0; j < kXLoads; ++j) sr.xv[j] = *reinterpret_cast<const u32x4*>(xrow[j] + kx);
@@ -372,9 +374,18 @@ void gemm_w4a16_tiled_kernel(
   const int k_end = (int)((int64_t)stages * (blockIdx.z + 1) / gridDim.z) * kTileK;
   StageRegs sr;
   fetch(sr, k_begin);
+  fetch_x(sr, k_begin);
   __builtin_assume(K >= kTileK);  // checked by the host
   for (int k_stage = k_begin; k_stage < k_end; k_stage += kTileK) {
     const int k0 = k_stage + 32 * half;
+    // the activations go to LDS first and their registers are asked for again at once, so the next
+    // stage's x (most of a stage's loads) has this stage's dequantisation and matrix instructions to arrive in
+#pragma unroll
+    for (int j = 0; j < kXLoads; ++j)  // rows 32 apart have the same row & 7
+      *reinterpret_cast<u32x4*>(&sm.b[32 * j + xr0][xunit ^ (xr0 & 7)]) = sr.xv[j];
+    asm volatile("" ::: "memory");
+    fetch_x(sr, k_stage + kTileK);
+    asm volatile("" ::: "memory");
     // dequantise the 32 weights: two 16-column blocks with their scale and selection
     const uint32_t cw[4] = {sr.cw4.x, sr.cw4.y, sr.cw4.z, sr.cw4.w};
 #pragma unroll
@@ -396,11 +407,8 @@ void gemm_w4a16_tiled_kernel(
       const int unit = (4 * half + u) ^ (lrow & 7);
       sm.a[lrow][unit] = make_uint4(a32[0], a32[1], a32[2], a32[3]);
     }
-#pragma unroll
-    for (int j = 0; j < kXLoads; ++j)  // rows 32 apart have the same row & 7
-      *reinterpret_cast<u32x4*>(&sm.b[32 * j + xr0][xunit ^ (xr0 & 7)]) = sr.xv[j];
     __syncthreads();
-    // the next stage's loads are in flight during the matrix instructions (the empty statements keep the
+    // the next stage's codes and scales are in flight during the matrix instructions (the empty statements keep the
     // compiler from moving them below)
     asm volatile("" ::: "memory");
     fetch(sr, k_stage + kTileK);
