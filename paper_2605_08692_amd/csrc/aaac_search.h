@@ -14,9 +14,16 @@
 // identical either way.
 //
 // The bucket table is replicated 32 times (one copy per LDS bank column) so
-// that data-dependent look-ups do not conflict; the 17 rows of {m, T, T, bin}
-// need no replication because distinct rows already sit in distinct banks.
+// that data-dependent look-ups do not conflict; the 16 rows of {m, T, T, bin}
+// of a table need no replication because distinct rows already sit in distinct
+// banks.  A pass that searches one table per weight (the table its group chose
+// earlier) and needs no reconstruction value reads 8-byte rows {m, bin}
+// instead: half the LDS cycles, and the two tables' rows then lie in different
+// halves of the banks, so lanes that search different tables do not collide
+// (with the 16-byte rows, which fill all banks once per table, they did: 9 % of
+// that pass's LDS cycles).
 #pragma once
+#include <cstddef>
 #include "aaac_device.h"
 
 namespace aaac {
@@ -26,7 +33,6 @@ constexpr int kSearchWaves = kSearchBlock / kWave;
 constexpr int kBuckets = 256;
 constexpr int kReplicas = 32;
 constexpr int kSlots = 32;          // histogram slots per bin; a bin is kSlots * 8 bytes
-constexpr int kPoison = 16;         // search row that holds NaN entries
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -36,10 +42,20 @@ struct alignas(16) SearchRow {  // 16 bytes: one LDS read serves a compare, a se
   uint32_t bin;     // (16 * table + i) * kSlots * 8: byte offset of the bin in a histogram
 };
 
+struct alignas(8) SearchRow8 {  // the same row for a search that needs the index only
+  float thr;        // midpoint m[i] (+inf for i = 15, NaN in the poisoned row)
+  uint32_t bin;
+};
+
 // Small search state; keep it at the start of the block's LDS so that its
 // offsets fit the 16-bit offset field of the DS instructions.
+// A bucket entry is the byte offset of its row from row[0][0]: 16 i for T0, 256 + 16 i for T1,
+// 512 / 528 for the two poisoned rows; half of it is the offset of the 8-byte row from row8[0][0].
 struct alignas(16) SearchTables {
-  SearchRow row[2][20];         // rows 0..15, poison row 16
+  SearchRow row[2][16];         // rows 0..15 of T0, then of T1
+  SearchRow poison[2];          // NaN entries; must follow row[][]
+  SearchRow8 row8[2][16];
+  SearchRow8 poison8[2];        // must follow row8[][]
   float lutpar[4];              // inv, off of bucket_row()
   int mid_bucket[2][16];        // bucket of each midpoint
   float newtab[32];             // the tables T0[16], T1[16], ascending
@@ -206,17 +222,22 @@ template <int REPL>
 __device__ __forceinline__ void assign_one_fast(const W8& x, float r, const SearchTables& st, const SearchLutT<REPL>& sl,
                                                 float inv, float off, uint32_t rep4_table, Lane8One& a) {
   const char* lut = reinterpret_cast<const char*>(sl.lut);
-  const char* rows = reinterpret_cast<const char*>(st.row[0]);
+  const char* rows = reinterpret_cast<const char*>(st.row8[0]);
+  // a row's midpoint is finite or +inf, the poisoned row's NaN: the sum is NaN iff some weight met it
   float check = 0.0f;
 #pragma unroll
   for (int p = 0; p < 8; ++p) {
     const float wn = x.w[p] * r;
     a.wn[p] = wn;
     const uint32_t e = *reinterpret_cast<const uint32_t*>(lut + (bucket_offset<REPL>(wn, inv, off) | rep4_table));
-    const f32x4 s = *reinterpret_cast<const f32x4*>(rows + e);
-    a.k[p] = __float_as_uint(s.w);
-    a.m[p] = __builtin_amdgcn_ballot_w64(wn > s.x);
-    check += s.y;  // T[i]; NaN only in the poisoned row
+    uint2 s = *reinterpret_cast<const uint2*>(rows + (e >> 1));  // {m[i], bin}
+    // (both halves are wanted here: left alone the compiler reads them apart, the bin later, under the
+    // branch that uses it, and two 4-byte reads cost the LDS what the 16-byte row did)
+    asm volatile("" : "+v"(s.x), "+v"(s.y));
+    const float thr = __uint_as_float(s.x);
+    a.k[p] = s.y;
+    a.m[p] = __builtin_amdgcn_ballot_w64(wn > thr);
+    check += thr;
   }
   a.check = check;
 }
@@ -241,15 +262,23 @@ __device__ __forceinline__ void assign_one_slow(const SearchTables& st, int tabl
 __device__ __forceinline__ void wave_make_rows(SearchTables& st) {
   const int lane = threadIdx.x & 63;
   __builtin_amdgcn_wave_barrier();
-  if (lane < 40) {
-    const int r = lane / 20, i = lane % 20;
+  static_assert(offsetof(SearchTables, poison) == 512 && offsetof(SearchTables, poison8) - offsetof(SearchTables, row8) == 256,
+                "bucket entries address the rows by these offsets");
+  if (lane < 32) {
+    const int r = lane >> 4, i = lane & 15;
     const float* T = st.newtab + 16 * r;
     SearchRow s;
     s.thr = i < 15 ? 0.5f * (T[i] + T[i + 1]) : __builtin_inff();
-    s.lo = i < 16 ? T[i] : __builtin_nanf("");
+    s.lo = T[i];
     s.hi = i < 15 ? T[i + 1] : __builtin_nanf("");
-    s.bin = (uint32_t)(16 * r + (i < 16 ? i : 0)) * (kSlots * 8u);
+    s.bin = (uint32_t)(16 * r + i) * (kSlots * 8u);
     st.row[r][i] = s;
+    st.row8[r][i] = SearchRow8{s.thr, s.bin};
+  } else if (lane < 34) {
+    const int r = lane - 32;
+    const uint32_t bin = (uint32_t)(16 * r) * (kSlots * 8u);
+    st.poison[r] = SearchRow{__builtin_inff(), __builtin_nanf(""), __builtin_nanf(""), bin};
+    st.poison8[r] = SearchRow8{__builtin_nanf(""), bin};
   }
   __builtin_amdgcn_wave_barrier();
   if (lane < 32) {
@@ -282,8 +311,8 @@ __device__ __forceinline__ void build_bucket_table(SearchTables& st, SearchLutT<
       below += bj < b ? 1 : 0;
       inside += bj == b ? 1 : 0;
     }
-    const uint32_t row = inside <= 1 ? (uint32_t)below : (uint32_t)kPoison;
-    const uint32_t e = 16u * row + (uint32_t)(r * sizeof(st.row[0]));
+    const uint32_t e = inside <= 1 ? 16u * (uint32_t)below + (uint32_t)(r * sizeof(st.row[0]))
+                                   : (uint32_t)(sizeof(st.row) + r * sizeof(SearchRow));
     if constexpr (REPL == 4) {  // the four copies are one 16-byte store: no staging, one barrier less
       *reinterpret_cast<uint4*>(&sl.lut[r][b * REPL]) = make_uint4(e, e, e, e);
     } else {
