@@ -13,6 +13,7 @@
 // keys whose prefix has a slot, looked up through small tables in LDS.
 // Everything here is integer work except the final interpolation, which is a
 // fixed sequence of fp64 operations.
+#include <type_traits>
 #include "aaac_device.h"
 #include "aaac_internal.h"
 
@@ -41,15 +42,23 @@ template <> struct PassBits<4> { static constexpr int shift = 0, bins = 16; };
 constexpr int kWaveQueue = 512;   // keys a wavefront can hold before it moves them to the candidate list
 constexpr int kQueueMove = 256;   // it moves them when it holds this many (looked at once per 32 weights of a lane)
 
+constexpr uint32_t kDeadSlot = kQuantSlots;  // in the LDS copies of the maps: "no wanted rank follows this prefix"
+
 struct QuantLds {
-  uint32_t hist[kQuantSlots * 256];  // pass 1 uses the first 4096 counters
+  // the slot maps, 0xFF ("not followed") turned into kDeadSlot; row kDeadSlot of map2 / map3 is all
+  // kDeadSlot, so a dead key walks through the maps without a test and is told apart at the end.
+  // They come first: their offsets then fit the 16-bit offset field of the LDS instructions.
   uint8_t map1[4096];
-  uint8_t map2[kQuantSlots][256];
-  uint8_t map3[kQuantSlots][256];
+  uint8_t map2[kQuantSlots + 1][256];
+  uint8_t map3[kQuantSlots + 1][256];
+  uint32_t hist[kQuantSlots * 256];  // pass 1 uses the first 4096 counters
   uint32_t queue[kQBlock / 64][kWaveQueue];  // pass 3: the keys each wavefront has found and not yet moved
   uint32_t queued[kQBlock / 64];             // how many
   uint32_t listed;                           // keys the block has moved to its part of the list
 };
+
+// four map bytes at once: 0xFF -> kDeadSlot (0x40), slots (< 0x40) unchanged
+__device__ __forceinline__ uint32_t dead_slots(uint32_t w) { return w ^ (((w & 0x80808080u) >> 7) * 0xBFu); }
 
 // One histogram pass.  The matrix is cut into 16-byte chunks (8 weights); block b
 // owns chunks [b * per_block, (b + 1) * per_block), a thread takes every 1024th.
@@ -57,11 +66,18 @@ struct QuantLds {
 // Pass 3 also writes every key it counts (a key whose first 20 bits some wanted rank still follows:
 // one weight in sixty or fewer) to the candidate list, and pass 4 then reads that list instead of
 // the weights.  Block b owns part b of the list (no global atomics: thousands of them on one counter
-// cost more than the pass); a wavefront collects its keys in LDS (position from an LDS atomic, which
-// only the few lanes with such a key execute) and moves them to the block's part when it holds 256.
-// Keys that find the wavefront's queue or the block's part full (many equal weights) are dropped and
-// cand_overflow is set: pass 4 then reads the weights like the other passes.
-template <int PASS>
+// cost more than the pass); a wavefront collects its keys in an LDS queue of its own (position from an
+// LDS atomic, which only the few lanes with such a key execute; positions from a ballot over the
+// lanes, with the fill count in a scalar register, measured 5 % slower) and moves them to the block's
+// part when it holds 256.  Keys that find the wavefront's queue or the block's part full (many equal
+// weights) are dropped and cand_overflow is set: pass 4 then reads the weights like the other passes.
+//
+// The passes are bound by their vector instructions and by the latency of the dependent LDS reads, so
+// the loop over the weights is kept lean: whole batches of four chunks per lane run without any test
+// of validity, addresses advance by pointer increments, and the maps need no "not followed" test
+// between levels.  CONTIG: the rows follow each other without padding (ldw == K), chunk e is then
+// at W + 8 e and its group is numbered like its weights.
+template <int PASS, bool CONTIG>
 __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __restrict__ W,
                                                              const float* __restrict__ rinv, int64_t N, int K,
                                                              int64_t ldw, int gshift, int64_t per_block,
@@ -78,58 +94,23 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
   uint32_t* const part = cand + (size_t)blockIdx.x * part_cap;
   if (PASS >= 2)
     for (int i = tid; i < 4096 / 4; i += kQBlock)
-      reinterpret_cast<uint32_t*>(sm.map1)[i] = reinterpret_cast<const uint32_t*>(qs->map1)[i];
-  if (PASS >= 3)
+      reinterpret_cast<uint32_t*>(sm.map1)[i] = dead_slots(reinterpret_cast<const uint32_t*>(qs->map1)[i]);
+  if (PASS >= 3) {
     for (int i = tid; i < kQuantSlots * 256 / 4; i += kQBlock)
-      reinterpret_cast<uint32_t*>(&sm.map2[0][0])[i] = reinterpret_cast<const uint32_t*>(&qs->map2[0][0])[i];
-  if (PASS >= 4)
+      reinterpret_cast<uint32_t*>(&sm.map2[0][0])[i] = dead_slots(reinterpret_cast<const uint32_t*>(&qs->map2[0][0])[i]);
+    if (tid < 64) reinterpret_cast<uint32_t*>(&sm.map2[kQuantSlots][0])[tid] = kDeadSlot * 0x01010101u;
+  }
+  if (PASS >= 4) {
     for (int i = tid; i < kQuantSlots * 256 / 4; i += kQBlock)
-      reinterpret_cast<uint32_t*>(&sm.map3[0][0])[i] = reinterpret_cast<const uint32_t*>(&qs->map3[0][0])[i];
+      reinterpret_cast<uint32_t*>(&sm.map3[0][0])[i] = dead_slots(reinterpret_cast<const uint32_t*>(&qs->map3[0][0])[i]);
+    if (tid < 64) reinterpret_cast<uint32_t*>(&sm.map3[kQuantSlots][0])[tid] = kDeadSlot * 0x01010101u;
+  }
   __syncthreads();
 
-  // Counts the 8 keys of a lane (bit p of valid: key p is to be counted).  The look-ups of the 8 keys
-  // go out together; a key that is not followed (0xFF) reads the next map at slot 63 and drops what
-  // it finds.
+  // The wavefront's queue (pass 3); move_queue() moves its keys to the block's part of the list when it
+  // holds `least` or more.  All 64 lanes call it together.
   uint32_t* const queue = sm.queue[wave];
   bool dropped = false;
-  auto count_keys = [&](const uint32_t (&key)[8], const uint32_t valid) {
-    if (PASS == 1) {
-#pragma unroll
-      for (int p = 0; p < 8; ++p)
-        if ((valid >> p) & 1u) atomicAdd(&sm.hist[key[p] >> 20], 1u);
-      return;
-    }
-    uint32_t slot[8];
-#pragma unroll
-    for (int p = 0; p < 8; ++p) slot[p] = sm.map1[key[p] >> 20];
-    if (PASS >= 3) {
-      uint32_t next[8];
-#pragma unroll
-      for (int p = 0; p < 8; ++p) next[p] = sm.map2[slot[p] & 63u][(key[p] >> 12) & 0xFFu];
-#pragma unroll
-      for (int p = 0; p < 8; ++p) slot[p] = slot[p] == 0xFFu ? 0xFFu : next[p];
-    }
-    if (PASS >= 4) {
-      uint32_t next[8];
-#pragma unroll
-      for (int p = 0; p < 8; ++p) next[p] = sm.map3[slot[p] & 63u][(key[p] >> 4) & 0xFFu];
-#pragma unroll
-      for (int p = 0; p < 8; ++p) slot[p] = slot[p] == 0xFFu ? 0xFFu : next[p];
-    }
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      if (((valid >> p) & 1u) && slot[p] != 0xFFu) {
-        atomicAdd(&sm.hist[slot[p] * kBins + ((key[p] >> PassBits<PASS>::shift) & (kBins - 1u))], 1u);
-        if (PASS == 3) {
-          const uint32_t at = atomicAdd(&sm.queued[wave], 1u);
-          if (at < (uint32_t)kWaveQueue) queue[at] = key[p];
-          else dropped = true;
-        }
-      }
-    }
-  };
-  // Moves the wavefront's keys to the block's part of the list when it holds `least` or more; all 64
-  // lanes call it together.
   auto move_queue = [&](const uint32_t least) {
     __builtin_amdgcn_wave_barrier();
     uint32_t n = sm.queued[wave];  // one address: the same value in every lane
@@ -145,6 +126,39 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
     if (lane == 0) sm.queued[wave] = 0u;
     __builtin_amdgcn_wave_barrier();
   };
+  // Counts the 8 keys of a lane; all_valid: every key counts, else bit p of valid says whether key p
+  // does.  The look-ups of the 8 keys go out together.
+  auto count_keys = [&](const uint32_t (&key)[8], auto all_valid, const uint32_t valid) {
+    constexpr bool kAll = decltype(all_valid)::value;
+    if (PASS == 1) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+        if (kAll || ((valid >> p) & 1u)) atomicAdd(&sm.hist[key[p] >> 20], 1u);
+      return;
+    }
+    uint32_t slot[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) slot[p] = sm.map1[key[p] >> 20];
+    if (PASS >= 3) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) slot[p] = sm.map2[slot[p]][(key[p] >> 12) & 0xFFu];
+    }
+    if (PASS >= 4) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) slot[p] = sm.map3[slot[p]][(key[p] >> 4) & 0xFFu];
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      if ((kAll || ((valid >> p) & 1u)) && slot[p] != kDeadSlot) {
+        atomicAdd(&sm.hist[slot[p] * kBins + ((key[p] >> PassBits<PASS>::shift) & (kBins - 1u))], 1u);
+        if (PASS == 3) {
+          const uint32_t at = atomicAdd(&sm.queued[wave], 1u);
+          if (at < (uint32_t)kWaveQueue) queue[at] = key[p];
+          else dropped = true;
+        }
+      }
+    }
+  };
 
   if (PASS == 4 && qs->cand_overflow == 0u) {
     // the candidate list holds every key that can still matter (this block reads the part that the
@@ -155,7 +169,7 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
 #pragma unroll
       for (int p = 0; p < 8; ++p) key[p] = part[i + p < n ? i + p : i];
       const uint32_t left = n - i;  // a key past the end repeats key i and is not counted
-      count_keys(key, left >= 8u ? 0xFFu : (1u << left) - 1u);
+      count_keys(key, std::false_type{}, left >= 8u ? 0xFFu : (1u << left) - 1u);
     }
   } else {
     const int cpr = K / 8;  // chunks per row
@@ -164,46 +178,66 @@ __global__ __launch_bounds__(kQBlock) void quant_hist_kernel(const uint16_t* __r
     const int64_t begin = (int64_t)blockIdx.x * per_block;
     int64_t end = begin + per_block;
     if (end > total) end = total;
+    // this lane's chunk: (row, c), the address of its weights; +1024 chunks per step, by increments
     int64_t e = begin + tid;
-    int64_t row = e / cpr;
-    int c = (int)(e - row * cpr);
+    int row = (int)(e / cpr);
+    int c = (int)(e - (int64_t)row * cpr);
+    const uint16_t* wp = W + (int64_t)row * ldw + c * 8;
     const int step_rows = kQBlock / cpr, step_c = kQBlock % cpr;
-    // Four chunks are asked for together (a thread has few chunks, and waiting for each before asking
-    // for the next left the pass bound by memory latency); the loads are unconditional, a chunk beyond
-    // the block's range reads the batch's first chunk again (the layer's first, when that is beyond
-    // the range too) and is not counted.  The loop runs the same number of times in every lane of a
-    // wavefront, because in pass 3 the lanes move their keys to the list together.
-    constexpr int kBatch = 4;
-    for (int64_t we = begin + (tid & ~63); we < end; we += kBatch * kQBlock, e += kBatch * kQBlock) {
-      int64_t rows[kBatch];
-      int cs[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        rows[u] = row;
-        cs[u] = c;
-        row += step_rows;
-        c += step_c;
-        if (c >= cpr) { c -= cpr; ++row; }
+    const int64_t wstep = (int64_t)step_rows * ldw + step_c * 8, wwrap = ldw - (int64_t)cpr * 8;
+    auto advance = [&]() {
+      if (CONTIG) {
+        wp += (int64_t)kQBlock * 8;
+        return;
       }
+      row += step_rows;
+      c += step_c;
+      wp += wstep;
+      if (c >= cpr) { c -= cpr; ++row; wp += wwrap; }
+    };
+    auto scale_index = [&]() -> int64_t {  // of the chunk's reciprocal scale
+      if (CONTIG) return ((int64_t)(wp - W)) >> gshift;
+      return (int64_t)row * Gs + ((c * 8) >> gshift);
+    };
+    auto keys_of = [&](const uint4 v, const float r, uint32_t (&key)[8]) {
+      const W8 w = unpack8(v);
+#pragma unroll
+      for (int p = 0; p < 8; ++p) key[p] = order_key(w.w[p] * r);
+    };
+    // Whole batches: four chunks per lane asked for together (a thread has few chunks, and waiting for
+    // each before asking for the next left the pass bound by memory latency), all of them inside the
+    // block's range for every lane of the wavefront, so nothing is tested.  The loop runs the same
+    // number of times in every lane of a wavefront (in pass 3 the lanes move their keys together).
+    constexpr int kBatch = 4;
+    int64_t we = begin + (tid & ~63);  // lane 0's chunk
+    for (; we + (kBatch - 1) * kQBlock + 63 < end; we += kBatch * kQBlock, e += kBatch * kQBlock) {
       uint4 v[kBatch];
       float r[kBatch];
-      bool ok[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
-        ok[u] = e + (int64_t)u * kQBlock < end;
-        const int64_t ru = ok[u] ? rows[u] : (ok[0] ? rows[0] : 0);
-        const int col = (ok[u] ? cs[u] : (ok[0] ? cs[0] : 0)) * 8;
-        v[u] = *reinterpret_cast<const uint4*>(W + ru * ldw + col);
-        r[u] = rinv[ru * Gs + (col >> gshift)];
+        v[u] = *reinterpret_cast<const uint4*>(wp);
+        r[u] = rinv[scale_index()];
+        advance();
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
-        const W8 w = unpack8(v[u]);
         uint32_t key[8];
-#pragma unroll
-        for (int p = 0; p < 8; ++p) key[p] = order_key(w.w[p] * r[u]);
-        count_keys(key, ok[u] ? 0xFFu : 0u);
+        keys_of(v[u], r[u], key);
+        count_keys(key, std::true_type{}, 0xFFu);
       }
+      if (PASS == 3) move_queue(kQueueMove);
+    }
+    // The rest, a chunk at a time; a lane past the end reads the block's first chunk and counts nothing.
+    const uint16_t* const wp_first = W + (begin / cpr) * ldw + (begin % cpr) * 8;
+    const int64_t r_first = (begin / cpr) * Gs + (((begin % cpr) * 8) >> gshift);
+    for (; we < end; we += kQBlock, e += kQBlock) {
+      const bool ok = e < end;
+      const uint4 v = *reinterpret_cast<const uint4*>(ok ? wp : wp_first);
+      const float r = rinv[ok ? scale_index() : r_first];
+      advance();
+      uint32_t key[8];
+      keys_of(v, r, key);
+      count_keys(key, std::false_type{}, ok ? 0xFFu : 0u);
       if (PASS == 3) move_queue(kQueueMove);
     }
     if (PASS == 3) {
@@ -457,8 +491,12 @@ hipError_t launch_quantile_init(const void* W, int64_t N, int64_t K, int64_t ldw
   const int64_t per_block = ceil_div(ceil_div(chunks, blocks), kQBlock) * kQBlock;
   blocks = ceil_div(chunks, per_block);
 #define AAAC_QPASS(P)                                                                                          \
-  quant_hist_kernel<P><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, qs, \
-                                                                 cand, (unsigned long long)cand_cap);          \
+  if (ldw == K)                                                                                                \
+    quant_hist_kernel<P, true><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, \
+                                                                         qs, cand, (unsigned long long)cand_cap); \
+  else                                                                                                         \
+    quant_hist_kernel<P, false><<<(unsigned)blocks, kQBlock, 0, stream>>>(Wp, rinv, N, (int)K, ldw, gshift, per_block, \
+                                                                          qs, cand, (unsigned long long)cand_cap); \
   if ((e = hipGetLastError()) != hipSuccess) return e;                                                         \
   quant_select_kernel<P><<<1, kQBlock, 0, stream>>>(qs, tg, grid_out);                                         \
   if ((e = hipGetLastError()) != hipSuccess) return e;
