@@ -175,6 +175,38 @@ def test_scale_codes_cover_every_e4m3_boundary():
     assert (host(scales).view(np.uint16) == rs).all() and (host(codes) == rc).all()
 
 
+
+@pytest.mark.parametrize("fmt,g", [(A.NVFP4, 16), (A.INT4, 128), (A.INT4, 32)])
+def test_scales_and_codes_for_every_bf16_absmax(fmt, g):
+    """A group's absmax is a bf16 value, so these 32,639 groups are every finite input that the
+    scale's division (absmax / 6, absmax / 7) and the reciprocal 1 / s can meet; the other weights
+    of a group are fractions of the absmax, so their codes depend on the rounded reciprocal."""
+    say(f"[scales] every bf16 absmax, fmt={fmt} g={g}")
+    amax = np.arange(1, 0x7F80, dtype=np.uint16)                       # all positive finite bf16 values
+    n = amax.size
+    rng = np.random.default_rng(31 + g)
+    frac = rng.uniform(-1.0, 1.0, (n, g)).astype(np.float32)
+    Wf = frac * (amax.astype(np.uint32) << 16).view(np.float32)[:, None]
+    Wt = torch.from_numpy(Wf).to(torch.bfloat16)
+    Wb = Wt.view(torch.int16).numpy().view(np.uint16).copy()
+    pos = rng.integers(0, g, n)
+    Wb[np.arange(n), pos] = amax | (rng.integers(0, 2, n).astype(np.uint16) << 15)   # the absmax itself, either sign
+    rows = 128                                                          # groups per row: K = 128 g
+    pad = (-n) % rows
+    Wb = np.concatenate([Wb, np.zeros((pad, g), np.uint16)]).reshape(-1, rows * g)
+    Wt = inputs.from_bits(Wb, DEV)
+    K = Wb.shape[1]
+    I = torch.rand(K, device=DEV, generator=seeded(977 + g)) + 0.1
+    tb = torch.from_numpy(oracle.fit(Wb[:4], g, fmt, np.ones(K, np.float32), inputs.format_grid(fmt), 0)["tables_bf16"].view(np.int16)).to(DEV)
+    codes, scales = A.aaac_encode(Wt, g, fmt, I, tb)
+    What = A.aaac_dequant(codes, scales, tb, g, fmt)
+    torch.cuda.synchronize()
+    rc, rs = oracle.encode(Wb, g, fmt, host(I), host(tb).view(np.uint16))
+    sc = host(scales) if fmt == A.NVFP4 else host(scales).view(np.uint16)
+    assert (sc == rs).all()
+    assert (host(codes) == rc).all()
+    assert (u16(What) == oracle.dequant(rc, rs, host(tb).view(np.uint16), g, fmt)).all()
+
 @pytest.mark.parametrize("case", GOLD["cases"], ids=lambda c: c["name"])
 def test_worked_vectors_on_gpu(case):
     from test_oracle_method import FMT, case_arrays, unpack
